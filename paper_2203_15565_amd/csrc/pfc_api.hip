@@ -1,0 +1,229 @@
+// Context management, argument checks and the extern "C" layer of libpfc.so.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "pfc_common.h"
+
+namespace pfc {
+
+static thread_local char g_hip_err[512] = "";
+
+void set_hip_error(hipError_t e, const char* what) {
+  snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
+}
+
+static const char* const kKernelNames[KID_COUNT] = {
+    "sample_init",   "sample_mark",  "sample_hist0", "sample_scan0", "sample_hist1",
+    "sample_scan1",  "sample_hist2", "sample_scan2", "sample_count", "sample_blkscan",
+    "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_logits",
+    "row_combine",   "loss_reduce",  "make_xst",     "gemm_dweight", "dweight_label",
+    "gemm_dfeatures", "dfeatures_final", "update"};
+
+static int64_t ceil_rN(int64_t N, double r) { return (int64_t)ceil(r * (double)N); }
+
+}  // namespace pfc
+
+using namespace pfc;
+
+extern "C" {
+
+int64_t pfc_num_sampled(int64_t N, int32_t B, double r) {
+  if (N < 1 || N >= (int64_t)1 << 31 || B < 1 || !(r > 0.0) || !(r <= 1.0)) return -1;
+  int64_t c = ceil_rN(N, r);
+  if (c > N) c = N;
+  int64_t b = B < N ? B : N;
+  return c > b ? c : b;
+}
+
+const char* pfc_strerror(int code) {
+  switch (code) {
+    case PFC_OK: return "ok";
+    case PFC_EINVAL: return "invalid argument";
+    case PFC_ELABEL: return "label or index out of range on the device";
+    case PFC_EHIP: return "HIP runtime error";
+    case PFC_ENOMEM: return "device memory allocation failed";
+    default: return "unknown error code";
+  }
+}
+
+const char* pfc_last_hip_error(void) { return g_hip_err; }
+
+static int dev_alloc(void** p, size_t bytes) {
+  *p = nullptr;
+  hipError_t e = hipMalloc(p, bytes ? bytes : 16);
+  if (e != hipSuccess) {
+    set_hip_error(e, "hipMalloc");
+    (void)hipGetLastError();
+    return PFC_ENOMEM;
+  }
+  return PFC_OK;
+}
+
+int pfc_destroy(pfc_ctx* c) {
+  if (!c) return PFC_EINVAL;
+  (void)hipStreamSynchronize(c->stream);
+  void* bufs[] = {c->pos_bits, c->hist, c->sel, c->blk_cnt, c->blk_off, c->err_flag, c->Xn,
+                  c->XsT, c->rnormX, c->Wn, c->WnT, c->rnormW, c->E, c->ET, c->rowpart,
+                  c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart};
+  for (void* b : bufs)
+    if (b) (void)hipFree(b);
+  if (c->host_pin) (void)hipHostFree(c->host_pin);
+  for (int i = 0; i < KID_COUNT; ++i) {
+    if (c->ev0[i]) (void)hipEventDestroy(c->ev0[i]);
+    if (c->ev1[i]) (void)hipEventDestroy(c->ev1[i]);
+  }
+  delete c;
+  return PFC_OK;
+}
+
+int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
+               int32_t precision, void* hip_stream) {
+  if (!out) return PFC_EINVAL;
+  *out = nullptr;
+  if (N < 1 || N >= (int64_t)1 << 31) return PFC_EINVAL;
+  if (D < 256 || D > 1024 || D % 256 != 0) return PFC_EINVAL;
+  if (B_max < 1 || B_max > (1 << 20)) return PFC_EINVAL;
+  if (!(r_max > 0.0) || !(r_max <= 1.0)) return PFC_EINVAL;
+  if (precision != PFC_PRECISION_FP32 && precision != PFC_PRECISION_BF16) return PFC_EINVAL;
+
+  pfc_ctx* c = new (std::nothrow) pfc_ctx;
+  if (!c) return PFC_ENOMEM;
+  memset(c, 0, sizeof(*c));
+  c->N = N;
+  c->D = D;
+  c->B_max = B_max;
+  c->r_max = r_max;
+  c->precision = precision;
+  c->stream = (hipStream_t)hip_stream;
+  c->k_cap = pfc_num_sampled(N, B_max, r_max);
+  c->kp_cap = round_up(c->k_cap, kPadK);
+  c->Bp_cap = (int32_t)round_up(B_max, kPadB);
+  c->esize = precision == PFC_PRECISION_BF16 ? 2 : 4;
+
+  const size_t es = c->esize;
+  const size_t Bp = (size_t)c->Bp_cap, kp = (size_t)c->kp_cap, Dz = (size_t)D;
+  c->nblk_cap = (int32_t)((N + 2047) / 2048);
+  int rc = PFC_OK;
+#define ALLOC(field, bytes)                                  \
+  if (rc == PFC_OK) rc = dev_alloc((void**)&c->field, (bytes))
+  ALLOC(pos_bits, ((size_t)(N + 31) / 32 + 64) * 4);
+  ALLOC(hist, 3 * 2048 * 4);
+  ALLOC(sel, sizeof(SelState));
+  ALLOC(blk_cnt, (size_t)c->nblk_cap * 2 * 4);
+  ALLOC(blk_off, (size_t)c->nblk_cap * 2 * 4);
+  ALLOC(err_flag, 16);
+  ALLOC(Xn, Bp * Dz * es);
+  ALLOC(XsT, Bp * Dz * es);
+  ALLOC(rnormX, Bp * 4);
+  ALLOC(Wn, kp * Dz * es);
+  ALLOC(WnT, kp * Dz * es);
+  ALLOC(rnormW, kp * 4);
+  ALLOC(E, Bp * kp * es);
+  ALLOC(ET, Bp * kp * es);
+  ALLOC(rowpart, (kp / kPadK) * 2 * Bp * 4);
+  ALLOC(clabel, Bp * 4);
+  ALLOC(rowscale, Bp * 4);
+  ALLOC(dlabel, Bp * 4);
+  ALLOC(lossrow, Bp * 4);
+  ALLOC(dXpart, (size_t)kMaxSplits * Bp * Dz * 4);
+#undef ALLOC
+  if (rc == PFC_OK) {
+    hipError_t e = hipHostMalloc((void**)&c->host_pin, 64, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      set_hip_error(e, "hipHostMalloc");
+      rc = PFC_ENOMEM;
+    }
+  }
+  if (rc == PFC_OK) {
+    hipError_t e = hipMemsetAsync(c->err_flag, 0, 16, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+      set_hip_error(e, "hipMemsetAsync(err_flag)");
+      rc = PFC_EHIP;
+    }
+  }
+  if (rc != PFC_OK) {
+    pfc_destroy(c);
+    return rc;
+  }
+  *out = c;
+  return PFC_OK;
+}
+
+int pfc_check(pfc_ctx* c) {
+  if (!c) return PFC_EINVAL;
+  PFC_HIP(hipMemcpyAsync(c->host_pin + 8, c->err_flag, 4, hipMemcpyDeviceToHost, c->stream));
+  PFC_HIP(hipStreamSynchronize(c->stream));
+  if (c->host_pin[8] != 0) {
+    PFC_HIP(hipMemsetAsync(c->err_flag, 0, 4, c->stream));
+    PFC_HIP(hipStreamSynchronize(c->stream));
+    return PFC_ELABEL;
+  }
+  return PFC_OK;
+}
+
+int pfc_set_timing(pfc_ctx* c, int32_t enabled) {
+  if (!c) return PFC_EINVAL;
+  if (enabled && !c->ev0[0]) {
+    for (int i = 0; i < KID_COUNT; ++i) {
+      PFC_HIP(hipEventCreate(&c->ev0[i]));
+      PFC_HIP(hipEventCreate(&c->ev1[i]));
+    }
+  }
+  c->timing = enabled ? 1 : 0;
+  memset(c->ev_used, 0, sizeof(c->ev_used));
+  return PFC_OK;
+}
+
+int pfc_get_timing(pfc_ctx* c, const char** names_out, float* ms_out, int32_t cap) {
+  if (!c || !names_out || !ms_out || cap < 0) return PFC_EINVAL;
+  PFC_HIP(hipStreamSynchronize(c->stream));
+  int n = 0;
+  for (int i = 0; i < KID_COUNT && n < cap; ++i) {
+    if (!c->ev_used[i]) continue;
+    float ms = 0.f;
+    PFC_HIP(hipEventElapsedTime(&ms, c->ev0[i], c->ev1[i]));
+    names_out[n] = kKernelNames[i];
+    ms_out[n] = ms;
+    ++n;
+  }
+  return n;
+}
+
+int pfc_sample_masked(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t seed,
+                      uint64_t step, uint32_t score_mask, int32_t* idx_out, int32_t* yl_out,
+                      int64_t* k_out) {
+  if (!c || !labels || !idx_out || !yl_out || !k_out) return PFC_EINVAL;
+  if (B < 1 || B > c->B_max) return PFC_EINVAL;
+  if (!(r > 0.0) || !(r <= 1.0) || r > c->r_max) return PFC_EINVAL;
+  return sample_impl(c, labels, B, r, seed, step, score_mask, idx_out, yl_out, k_out);
+}
+
+int pfc_sample(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t seed,
+               uint64_t step, int32_t* idx_out, int32_t* yl_out, int64_t* k_out) {
+  return pfc_sample_masked(c, labels, B, r, seed, step, 0xFFFFFFFFu, idx_out, yl_out, k_out);
+}
+
+int pfc_forward_backward(pfc_ctx* c, const float* X, const float* W, const int32_t* idx,
+                         int64_t k, const int32_t* yl, int32_t B, float s, float m,
+                         float* loss_out, float* dX_out, float* dW_out) {
+  if (!c || !X || !W || !idx || !yl || !loss_out || !dX_out || !dW_out) return PFC_EINVAL;
+  if (B < 1 || B > c->B_max) return PFC_EINVAL;
+  if (k < 1 || k > c->k_cap || k > c->N) return PFC_EINVAL;
+  if (!(s > 0.f) || !(s <= 64.f)) return PFC_EINVAL;
+  if (!(m >= 0.f) || !(m < 3.14159265f)) return PFC_EINVAL;
+  return forward_backward_impl(c, X, W, idx, k, yl, B, s, m, loss_out, dX_out, dW_out);
+}
+
+int pfc_update(pfc_ctx* c, float* W, float* v, const int32_t* idx, int64_t k, const float* dW,
+               float lr, float mu) {
+  if (!c || !W || !v || !idx || !dW) return PFC_EINVAL;
+  if (k < 1 || k > c->N) return PFC_EINVAL;
+  if (!(lr == lr) || !(mu == mu)) return PFC_EINVAL;
+  return update_impl(c, W, v, idx, k, dW, lr, mu);
+}
+
+}  // extern "C"

@@ -1,0 +1,171 @@
+// Shared host/device declarations of libpfc.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pfc.h"
+
+namespace pfc {
+
+// ---------------------------------------------------------------------------------------------
+// Padded problem geometry.  Every scratch operand of the three GEMMs is padded with zeros to a
+// whole number of tiles, so the GEMM main loops need no bounds checks.
+// ---------------------------------------------------------------------------------------------
+constexpr int kPadB = 128;   // batch rows are padded to a multiple of this
+constexpr int kPadK = 256;   // sampled rows are padded to a multiple of this
+constexpr int kMaxSplits = 64;
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// Kernel ids for the optional per-kernel timing.
+enum KernelId {
+  KID_SAMPLE_INIT = 0,
+  KID_SAMPLE_MARK,
+  KID_SAMPLE_HIST0,
+  KID_SAMPLE_SCAN0,
+  KID_SAMPLE_HIST1,
+  KID_SAMPLE_SCAN1,
+  KID_SAMPLE_HIST2,
+  KID_SAMPLE_SCAN2,
+  KID_SAMPLE_COUNT,
+  KID_SAMPLE_BLKSCAN,
+  KID_SAMPLE_WRITE,
+  KID_SAMPLE_REMAP,
+  KID_NORM_X,
+  KID_GATHER_W,
+  KID_GEMM_LOGITS,
+  KID_ROW_COMBINE,
+  KID_LOSS_REDUCE,
+  KID_MAKE_XST,
+  KID_GEMM_DW,
+  KID_DW_LABEL,
+  KID_GEMM_DX,
+  KID_DX_FINAL,
+  KID_UPDATE,
+  KID_COUNT
+};
+
+// State of the radix select, kept in device memory between the sampler's kernels.
+struct SelState {
+  uint32_t U;        // number of distinct labels (positives)
+  uint32_t k;        // |S| = max(U, ceil(r*N))
+  uint32_t need;     // negatives still to be taken inside the current prefix bin
+  uint32_t prefix;   // threshold bits fixed so far (in place, low bits zero)
+  uint32_t none;     // 1: no negative is taken at all (k == U)
+  uint32_t total;    // number of ids written (must equal k)
+  uint32_t pad[2];
+};
+
+}  // namespace pfc
+
+struct pfc_ctx {
+  int64_t N;
+  int32_t D;
+  int32_t B_max;
+  double r_max;
+  int32_t precision;
+  hipStream_t stream;
+
+  int64_t k_cap;    // pfc_num_sampled(N, B_max, r_max)
+  int64_t kp_cap;   // padded
+  int32_t Bp_cap;   // padded
+  size_t esize;     // bytes per GEMM operand element (4 or 2)
+
+  // sampler scratch
+  uint32_t* pos_bits;     // ceil(N/32) words (+ slack): bit j set <=> class j is in the batch
+  uint32_t* hist;         // 3 x 2048 bins
+  pfc::SelState* sel;
+  uint32_t* blk_cnt;      // 2 x nblk: per block (#sure, #equal-to-threshold)
+  uint32_t* blk_off;      // 2 x nblk: per block (output offset, #equal before)
+  int32_t nblk_cap;
+  int32_t* err_flag;      // device: nonzero once a bad label / index was seen
+  uint32_t* host_pin;     // pinned host words for read-backs
+
+  // forward/backward scratch (T = float or bf16 according to precision)
+  void* Xn;        // [Bp x D]   normalised features
+  void* XsT;       // [D x Bp]   (s/(B*l_i)) * xn_i, transposed
+  float* rnormX;   // [Bp]
+  void* Wn;        // [kp x D]   normalised sampled centers
+  void* WnT;       // [D x kp]
+  float* rnormW;   // [kp]
+  void* E;         // [Bp x kp]  exp(z), label column zeroed
+  void* ET;        // [kp x Bp]
+  float* rowpart;  // [tiles_j x Bp] partial row sums of exp(z)
+  float* clabel;   // [Bp] cosine of the label column
+  float* rowscale; // [Bp] s/(B*l_i)
+  float* dlabel;   // [Bp] (s/B)(p_iy - 1) rho_i
+  float* lossrow;  // [Bp]
+  float* dXpart;   // [splits x Bp x D]
+
+  // timing
+  int32_t timing;
+  hipEvent_t ev0[pfc::KID_COUNT];
+  hipEvent_t ev1[pfc::KID_COUNT];
+  uint8_t ev_used[pfc::KID_COUNT];
+};
+
+namespace pfc {
+
+void set_hip_error(hipError_t e, const char* what);
+
+#define PFC_HIP(expr)                                   \
+  do {                                                  \
+    hipError_t e__ = (expr);                            \
+    if (e__ != hipSuccess) {                            \
+      ::pfc::set_hip_error(e__, #expr);                 \
+      return PFC_EHIP;                                  \
+    }                                                   \
+  } while (0)
+
+// Launch helper: optional event pair around the kernel for the timing hooks.
+struct TimedLaunch {
+  pfc_ctx* c;
+  int id;
+  TimedLaunch(pfc_ctx* ctx, int kid) : c(ctx), id(kid) {
+    if (c->timing) (void)hipEventRecord(c->ev0[id], c->stream);
+  }
+  ~TimedLaunch() {
+    if (c->timing) {
+      (void)hipEventRecord(c->ev1[id], c->stream);
+      c->ev_used[id] = 1;
+    }
+  }
+};
+
+#define PFC_LAUNCH(ctx, kid, kernel, grid, block, shmem, ...)                          \
+  do {                                                                                 \
+    ::pfc::TimedLaunch tl__(ctx, kid);                                                 \
+    hipLaunchKernelGGL(kernel, grid, block, shmem, (ctx)->stream, __VA_ARGS__);        \
+  } while (0);                                                                         \
+  PFC_HIP(hipGetLastError())
+
+// entry points implemented per translation unit (called by the extern "C" layer)
+int sample_impl(pfc_ctx* ctx, const int64_t* labels, int32_t B, double r, uint64_t seed,
+                uint64_t step, uint32_t score_mask, int32_t* idx_out, int32_t* yl_out,
+                int64_t* k_out);
+int forward_backward_impl(pfc_ctx* ctx, const float* X, const float* W, const int32_t* idx,
+                          int64_t k, const int32_t* yl, int32_t B, float s, float m,
+                          float* loss_out, float* dX_out, float* dW_out);
+int update_impl(pfc_ctx* ctx, float* W, float* v, const int32_t* idx, int64_t k,
+                const float* dW, float lr, float mu);
+
+// ---------------------------------------------------------------------------------------------
+// Device helpers
+// ---------------------------------------------------------------------------------------------
+#if defined(__HIPCC__)
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T from_float(float x);
+template <>
+__device__ __forceinline__ float from_float<float>(float x) { return x; }
+template <>
+__device__ __forceinline__ __bf16 from_float<__bf16>(float x) { return (__bf16)x; }  // RNE
+#endif
+
+}  // namespace pfc

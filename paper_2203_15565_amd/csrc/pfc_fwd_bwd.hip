@@ -1,0 +1,552 @@
+// pfc_forward_backward: margin-softmax loss over the sampled centers and its gradients
+// (arXiv 2203.15565: Eq. 1 restricted to the sampled set S as in Eq. 4; Eq. 2 / Eq. 4 for the
+// feature gradient, the bracket of Eq. 3 for the center gradient).
+//
+// Pipeline (one stream, no host synchronisation):
+//   normalize_x        Xn = x/|x|                                   (HBM bound, tiny)
+//   gather_normalize_w Wn = W[idx]/|W[idx]|, plus its transpose     (HBM bound)
+//   gemm_logits        c = Wn Xn^T, margin, e = exp(s c) -> E, ET and per-tile row sums (MFMA)
+//   row_combine        l_i, lse_i, per-row loss, s/(B l_i), label-column coefficient
+//   loss_reduce        mean loss
+//   make_xst           XsT = ((s/(B l_i)) xn_i)^T
+//   gemm_dweight       dWn = E^T Xs  (off-label part)                (MFMA)
+//   dweight_label      adds the label-column term to the rows of positive classes (fp32)
+//   gemm_dfeatures     partial sums of E Wn over slices of S         (MFMA, split over S)
+//   dfeatures_final    reduce slices, scale, label term, project through x -> x/|x|
+//
+// Because cosines lie in [-1,1] and s <= 64, exp(s c) lies in [e^-64, e^64] and a row sum over
+// at most 2^31 classes stays below 3.4e38: exp needs no running maximum, and one fixed
+// reference (zero) serves every tile, so p_ij = E_ij / l_i with l_i known only after the GEMM.
+// The label column is kept out of E (stored as zero) and handled in fp32 on the side, where
+// (p - 1) and the margin derivative are formed without bf16 rounding.
+#include <math.h>
+
+#include "pfc_common.h"
+#include "pfc_gemm.h"
+
+namespace pfc {
+
+namespace {
+
+constexpr float kEpsNorm = 1e-12f;
+constexpr float kEpsSin2 = 1e-12f;
+
+// ---------------------------------------------------------------------------------------------
+// normalize_x: one wavefront per (padded) feature row.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void normalize_x_kernel(const float* __restrict__ X, int B, int Bp, int D,
+                                   const int32_t* __restrict__ yl, int64_t k, T* __restrict__ Xn,
+                                   float* __restrict__ rnormX, float* __restrict__ clabel,
+                                   int32_t* __restrict__ err_flag) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= Bp) return;
+  const int nchunk = D >> 8;   // float4 chunks per lane
+  float4 v[4];
+  float ss = 0.f;
+  if (i < B) {
+    for (int c = 0; c < nchunk; ++c) {
+      v[c] = *reinterpret_cast<const float4*>(X + (int64_t)i * D + c * 256 + lane * 4);
+      ss += v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
+    }
+  }
+  ss = wave_sum(ss);
+  const float rn = (i < B) ? 1.f / fmaxf(sqrtf(ss), kEpsNorm) : 0.f;
+  for (int c = 0; c < nchunk; ++c) {
+    T* dst = Xn + (int64_t)i * D + c * 256 + lane * 4;
+    if (i < B) {
+      dst[0] = from_float<T>(v[c].x * rn);
+      dst[1] = from_float<T>(v[c].y * rn);
+      dst[2] = from_float<T>(v[c].z * rn);
+      dst[3] = from_float<T>(v[c].w * rn);
+    } else {
+      dst[0] = dst[1] = dst[2] = dst[3] = from_float<T>(0.f);
+    }
+  }
+  if (lane == 0) {
+    rnormX[i] = rn;
+    clabel[i] = 0.f;
+    if (i < B) {
+      const int32_t y = yl[i];
+      if (y < 0 || (int64_t)y >= k) atomicOr(err_flag, 2);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// gather_normalize_w: a block owns RPB consecutive sampled rows.  Each wavefront normalises
+// RPB/4 rows (coalesced 2 KB row reads of W, ascending row ids), writes them to Wn and into an
+// LDS tile; the block then writes the tile transposed into WnT so that every store instruction
+// covers whole 128-byte segments.  Rows k..kp-1 are written as zeros.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int RPB>
+__global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N,
+                                          const int32_t* __restrict__ idx, int64_t k, int64_t kp,
+                                          int D, T* __restrict__ Wn, T* __restrict__ WnT,
+                                          float* __restrict__ rnormW,
+                                          int32_t* __restrict__ err_flag) {
+  extern __shared__ __align__(16) char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t j0 = (int64_t)blockIdx.x * RPB;
+  const int rowbytes = D * (int)sizeof(T) + 4;   // +4: transposed reads then spread over banks
+  const int nchunk = D >> 8;
+  for (int rr = wave; rr < RPB; rr += 4) {
+    const int64_t j = j0 + rr;
+    float4 v[4];
+    float ss = 0.f;
+    bool ok = false;
+    if (j < k) {
+      const int64_t row = idx[j];
+      ok = (row >= 0 && row < N);
+      if (!ok && lane == 0) atomicOr(err_flag, 4);
+      if (ok) {
+        for (int c = 0; c < nchunk; ++c) {
+          v[c] = *reinterpret_cast<const float4*>(W + row * D + c * 256 + lane * 4);
+          ss += v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
+        }
+      }
+    }
+    ss = wave_sum(ss);
+    const float rn = ok ? 1.f / fmaxf(sqrtf(ss), kEpsNorm) : 0.f;
+    if (lane == 0) rnormW[j] = rn;
+    for (int c = 0; c < nchunk; ++c) {
+      T o[4];
+      if (ok) {
+        o[0] = from_float<T>(v[c].x * rn);
+        o[1] = from_float<T>(v[c].y * rn);
+        o[2] = from_float<T>(v[c].z * rn);
+        o[3] = from_float<T>(v[c].w * rn);
+      } else {
+        o[0] = o[1] = o[2] = o[3] = from_float<T>(0.f);
+      }
+      const int d = c * 256 + lane * 4;
+      T* g = Wn + j * D + d;
+      T* sdst = reinterpret_cast<T*>(smem + rr * rowbytes) + d;
+      if constexpr (sizeof(T) == 2) {
+        uint2 pk;
+        __builtin_memcpy(&pk, o, 8);
+        *reinterpret_cast<uint2*>(g) = pk;
+        reinterpret_cast<uint32_t*>(sdst)[0] = pk.x;   // LDS rows are only 4-byte aligned
+        reinterpret_cast<uint32_t*>(sdst)[1] = pk.y;
+      } else {
+        float4 f4;
+        f4.x = (float)o[0]; f4.y = (float)o[1]; f4.z = (float)o[2]; f4.w = (float)o[3];
+        *reinterpret_cast<float4*>(g) = f4;
+        sdst[0] = o[0]; sdst[1] = o[1]; sdst[2] = o[2]; sdst[3] = o[3];
+      }
+    }
+  }
+  __syncthreads();
+  // transposed write-out: item (d, q) = 16 bytes = EPV consecutive rows q*EPV.. of column d
+  constexpr int EPV = 16 / (int)sizeof(T);
+  constexpr int QN = RPB / EPV;
+  const int items = D * QN;
+  for (int it = threadIdx.x; it < items; it += blockDim.x) {
+    const int q = it % QN, d = it / QN;
+    T o[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e)
+      o[e] = reinterpret_cast<const T*>(smem + (q * EPV + e) * rowbytes)[d];
+    uint4 pk;
+    __builtin_memcpy(&pk, o, 16);
+    *reinterpret_cast<uint4*>(WnT + (int64_t)d * kp + j0 + q * EPV) = pk;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// gemm_logits: tile of c[j][i] (rows = sampled classes, columns = samples), fused epilogue.
+// ---------------------------------------------------------------------------------------------
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
+    const typename Cfg::elem* __restrict__ Wn, const typename Cfg::elem* __restrict__ Xn, int D,
+    int64_t k, int B, int Bp, int64_t kp, const int32_t* __restrict__ yl, float s, float cos_m,
+    float sin_m, typename Cfg::elem* __restrict__ E, typename Cfg::elem* __restrict__ ET,
+    float* __restrict__ rowpart, float* __restrict__ clabel, int tiles_j, int tiles_i) {
+  using T = typename Cfg::elem;
+  extern __shared__ __align__(16) char smem[];
+  int tj, ti;
+  if (!xcd_tile(blockIdx.x, tiles_i, tiles_j, tj, ti)) return;
+  const int64_t j0 = (int64_t)tj * Cfg::BM;
+  const int i0 = ti * Cfg::BN;
+
+  f32x16 acc[Cfg::TM][Cfg::TN];
+#pragma unroll
+  for (int a = 0; a < Cfg::TM; ++a)
+#pragma unroll
+    for (int b = 0; b < Cfg::TN; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  gemm_tile_nt<Cfg>(Wn + j0 * D, D, Xn + (int64_t)i0 * D, D, D / Cfg::BK, smem, acc);
+
+  float colsum[Cfg::TN];
+#pragma unroll
+  for (int bn = 0; bn < Cfg::TN; ++bn) {
+    const int i = i0 + acc_col<Cfg>(bn);
+    const bool vi = i < B;
+    const int32_t y = vi ? yl[i] : -1;
+    float sum = 0.f;
+#pragma unroll
+    for (int bm = 0; bm < Cfg::TM; ++bm) {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        T pack[4];
+        const int64_t jb = j0 + acc_row<Cfg>(bm, g4 * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int64_t j = jb + e;
+          float c = acc[bm][bn][g4 * 4 + e];
+          c = fminf(fmaxf(c, -1.f), 1.f);
+          const bool lab = (j == (int64_t)y);
+          float z = s * c;
+          if (lab) z = s * (c * cos_m - sqrtf(fmaxf(1.f - c * c, 0.f)) * sin_m);
+          float ev = __expf(z);
+          if (!(vi && j < k)) ev = 0.f;
+          sum += ev;
+          if (lab && vi && j < k) {
+            clabel[i] = c;
+            ev = 0.f;
+          }
+          pack[e] = from_float<T>(ev);
+          ET[j * Bp + i] = pack[e];
+        }
+        T* edst = E + (int64_t)i * kp + jb;
+        if constexpr (sizeof(T) == 2) {
+          uint2 pk;
+          __builtin_memcpy(&pk, pack, 8);
+          *reinterpret_cast<uint2*>(edst) = pk;
+        } else {
+          uint4 pk;
+          __builtin_memcpy(&pk, pack, 16);
+          *reinterpret_cast<uint4*>(edst) = pk;
+        }
+      }
+    }
+    sum += __shfl_xor(sum, 32, 64);
+    colsum[bn] = sum;
+  }
+  // cross-wave reduction over the WM wavefronts that share a column (fixed order)
+  float* red = reinterpret_cast<float*>(smem);   // [WM][BN]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane < 32) {
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn)
+      red[(wave / Cfg::WN) * Cfg::BN + (wave % Cfg::WN) * Cfg::WTN + bn * 32 + lane] = colsum[bn];
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < Cfg::BN; t += Cfg::THREADS) {
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < Cfg::WM; ++w) v += red[w * Cfg::BN + t];
+    rowpart[(int64_t)tj * Bp + i0 + t] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// row_combine: l_i = sum over tiles (fixed order), then the per-row scalars.
+// Block = 32 rows x 32 partial summers.
+// ---------------------------------------------------------------------------------------------
+__global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_j, int B, int Bp,
+                                   const float* __restrict__ clabel, float s, float cos_m,
+                                   float sin_m, float* __restrict__ rowscale,
+                                   float* __restrict__ dlabel, float* __restrict__ lossrow) {
+  __shared__ float sm[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int i = blockIdx.x * 32 + tx;
+  float v = 0.f;
+  if (i < Bp)
+    for (int t = ty; t < tiles_j; t += 32) v += rowpart[(int64_t)t * Bp + i];
+  sm[ty][tx] = v;
+  __syncthreads();
+  if (ty == 0 && i < Bp) {
+    float l = 0.f;
+    for (int t = 0; t < 32; ++t) l += sm[t][tx];
+    if (i < B) {
+      const float c = clabel[i];
+      const float sin2 = 1.f - c * c;
+      const float zlab = s * (c * cos_m - sqrtf(fmaxf(sin2, 0.f)) * sin_m);
+      const float lse = logf(l);
+      const float p = __expf(zlab) / l;
+      const float rho = cos_m + c * sin_m / sqrtf(fmaxf(sin2, kEpsSin2));
+      const float invB = 1.f / (float)B;
+      lossrow[i] = lse - zlab;
+      rowscale[i] = s * invB / l;
+      dlabel[i] = s * invB * (p - 1.f) * rho;
+    } else {
+      lossrow[i] = 0.f;
+      rowscale[i] = 0.f;
+      dlabel[i] = 0.f;
+    }
+  }
+}
+
+__global__ void loss_reduce_kernel(const float* __restrict__ lossrow, int B,
+                                   float* __restrict__ loss_out) {
+  __shared__ float sm[256];
+  float v = 0.f;
+  for (int i = threadIdx.x; i < B; i += 256) v += lossrow[i];
+  sm[threadIdx.x] = v;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) loss_out[0] = sm[0] / (float)B;
+}
+
+// XsT[d][i] = (s/(B l_i)) * x_i[d]/|x_i| (zero for padded i); 32x32 LDS transpose.
+template <typename T>
+__global__ void make_xst_kernel(const float* __restrict__ X, int B, int Bp, int D,
+                                const float* __restrict__ rnormX,
+                                const float* __restrict__ rowscale, T* __restrict__ XsT) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  const int i0 = blockIdx.x * 32, d0 = blockIdx.y * 32;
+  for (int r = ty; r < 32; r += 8) {
+    const int i = i0 + r;
+    float v = 0.f;
+    if (i < B) v = X[(int64_t)i * D + d0 + tx] * rnormX[i] * rowscale[i];
+    tile[r][tx] = v;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8)
+    XsT[(int64_t)(d0 + r) * Bp + i0 + tx] = from_float<T>(tile[tx][r]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// gemm_dweight: dWn[j][d] = sum_i ET[j][i] * XsT[d][i]; rows j < k are written.
+// ---------------------------------------------------------------------------------------------
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_kernel(
+    const typename Cfg::elem* __restrict__ ET, const typename Cfg::elem* __restrict__ XsT, int D,
+    int64_t k, int Bp, float* __restrict__ dW, int tiles_j, int tiles_d) {
+  extern __shared__ __align__(16) char smem[];
+  int tj, td;
+  if (!xcd_tile(blockIdx.x, tiles_d, tiles_j, tj, td)) return;
+  const int64_t j0 = (int64_t)tj * Cfg::BM;
+  const int d0 = td * Cfg::BN;
+  f32x16 acc[Cfg::TM][Cfg::TN];
+#pragma unroll
+  for (int a = 0; a < Cfg::TM; ++a)
+#pragma unroll
+    for (int b = 0; b < Cfg::TN; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  gemm_tile_nt<Cfg>(ET + j0 * Bp, Bp, XsT + (int64_t)d0 * Bp, Bp, Bp / Cfg::BK, smem, acc);
+#pragma unroll
+  for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t j = j0 + acc_row<Cfg>(bm, r);
+      if (j < k) {
+#pragma unroll
+        for (int bn = 0; bn < Cfg::TN; ++bn)
+          dW[j * D + d0 + acc_col<Cfg>(bn)] = acc[bm][bn][r];
+      }
+    }
+}
+
+// dweight_label: dWn[y] += sum over samples i with label y of dlabel_i * xn_i, in ascending i.
+// Block i does the whole sum for its class if i is the first sample carrying that label.
+__global__ void dweight_label_kernel(const float* __restrict__ X, int B, int D,
+                                     const int32_t* __restrict__ yl, int64_t k,
+                                     const float* __restrict__ rnormX,
+                                     const float* __restrict__ dlabel, float* __restrict__ dW) {
+  const int i = blockIdx.x;
+  const int32_t y = yl[i];
+  if (y < 0 || (int64_t)y >= k) return;
+  int seen = 0;
+  for (int p = threadIdx.x; p < i; p += blockDim.x) seen |= (yl[p] == y);
+  if (__syncthreads_or(seen)) return;
+  float acc[8];
+  const int nc = D / 128;
+  for (int c = 0; c < nc; ++c) acc[c] = 0.f;
+  for (int p = i; p < B; ++p) {
+    if (yl[p] != y) continue;
+    const float a = dlabel[p] * rnormX[p];
+    for (int c = 0; c < nc; ++c) acc[c] += a * X[(int64_t)p * D + c * 128 + threadIdx.x];
+  }
+  for (int c = 0; c < nc; ++c) dW[(int64_t)y * D + c * 128 + threadIdx.x] += acc[c];
+}
+
+// ---------------------------------------------------------------------------------------------
+// gemm_dfeatures: slice `sp` of S: part[sp][i][d] = sum_{j in slice} E[i][j] * WnT[d][j].
+// ---------------------------------------------------------------------------------------------
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void gemm_dfeatures_kernel(
+    const typename Cfg::elem* __restrict__ E, const typename Cfg::elem* __restrict__ WnT, int D,
+    int Bp, int64_t kp, int slabs_total, int slabs_per, int splits, float* __restrict__ part,
+    int tiles_i, int tiles_d) {
+  extern __shared__ __align__(16) char smem[];
+  int sp, tile;
+  if (!xcd_tile(blockIdx.x, tiles_i * tiles_d, splits, sp, tile)) return;
+  const int ti = tile / tiles_d, td = tile % tiles_d;
+  const int i0 = ti * Cfg::BM, d0 = td * Cfg::BN;
+  const int slab0 = sp * slabs_per;
+  int ns = slabs_total - slab0;
+  if (ns > slabs_per) ns = slabs_per;
+  f32x16 acc[Cfg::TM][Cfg::TN];
+#pragma unroll
+  for (int a = 0; a < Cfg::TM; ++a)
+#pragma unroll
+    for (int b = 0; b < Cfg::TN; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  const int64_t koff = (int64_t)slab0 * Cfg::BK;
+  gemm_tile_nt<Cfg>(E + (int64_t)i0 * kp + koff, kp, WnT + (int64_t)d0 * kp + koff, kp, ns, smem,
+                    acc);
+  float* out = part + (int64_t)sp * Bp * D;
+#pragma unroll
+  for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int i = i0 + acc_row<Cfg>(bm, r);
+#pragma unroll
+      for (int bn = 0; bn < Cfg::TN; ++bn)
+        out[(int64_t)i * D + d0 + acc_col<Cfg>(bn)] = acc[bm][bn][r];
+    }
+}
+
+// dfeatures_final: one wavefront per sample.
+//   g  = (s/(B l_i)) * sum_slices part + dlabel_i * wn_{y_i}        (dL/d xn_i)
+//   dx = (g - <g, xn_i> xn_i) / |x_i|
+__global__ void dfeatures_final_kernel(const float* __restrict__ part, int splits, int B, int Bp,
+                                       int D, const float* __restrict__ X,
+                                       const float* __restrict__ W, int64_t N,
+                                       const int32_t* __restrict__ idx,
+                                       const int32_t* __restrict__ yl, int64_t k,
+                                       const float* __restrict__ rnormX,
+                                       const float* __restrict__ rnormW,
+                                       const float* __restrict__ rowscale,
+                                       const float* __restrict__ dlabel, float* __restrict__ dX) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= B) return;
+  const int nchunk = D >> 8;
+  const float rs = rowscale[i], rnx = rnormX[i], dl = dlabel[i];
+  const int32_t y = yl[i];
+  int64_t wrow = -1;
+  float rnw = 0.f;
+  if (y >= 0 && (int64_t)y < k) {
+    wrow = idx[y];
+    rnw = rnormW[y];
+    if (wrow < 0 || wrow >= N) wrow = -1;
+  }
+  float4 g[4], xn[4];
+  float u = 0.f;
+  for (int c = 0; c < nchunk; ++c) {
+    const int d = c * 256 + lane * 4;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int sp = 0; sp < splits; ++sp) {
+      const float4 t = *reinterpret_cast<const float4*>(part + ((int64_t)sp * Bp + i) * D + d);
+      a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+    }
+    a.x *= rs; a.y *= rs; a.z *= rs; a.w *= rs;
+    if (wrow >= 0) {
+      const float4 w = *reinterpret_cast<const float4*>(W + wrow * D + d);
+      const float f = dl * rnw;
+      a.x += f * w.x; a.y += f * w.y; a.z += f * w.z; a.w += f * w.w;
+    }
+    float4 x = *reinterpret_cast<const float4*>(X + (int64_t)i * D + d);
+    x.x *= rnx; x.y *= rnx; x.z *= rnx; x.w *= rnx;
+    g[c] = a;
+    xn[c] = x;
+    u += a.x * x.x + a.y * x.y + a.z * x.z + a.w * x.w;
+  }
+  u = wave_sum(u);
+  for (int c = 0; c < nchunk; ++c) {
+    float4 o;
+    o.x = (g[c].x - u * xn[c].x) * rnx;
+    o.y = (g[c].y - u * xn[c].y) * rnx;
+    o.z = (g[c].z - u * xn[c].z) * rnx;
+    o.w = (g[c].w - u * xn[c].w) * rnx;
+    *reinterpret_cast<float4*>(dX + (int64_t)i * D + c * 256 + lane * 4) = o;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t k,
+        const int32_t* yl, int32_t B, float s, float m, float* loss_out, float* dX_out,
+        float* dW_out) {
+  using CfgF = TileCfg<T, 256, 128, 2, 2>;   // logits: 256 classes x 128 samples
+  using CfgW = TileCfg<T, 256, 128, 2, 2>;   // dweight: 256 classes x 128 of D
+  using CfgX = TileCfg<T, 128, 128, 2, 2>;   // dfeatures: 128 samples x 128 of D
+  const int D = c->D;
+  const int Bp = (int)round_up(B, kPadB);
+  const int64_t kp = round_up(k, kPadK);
+  const float cos_m = cosf(m), sin_m = sinf(m);
+  T* Xn = (T*)c->Xn; T* XsT = (T*)c->XsT; T* Wn = (T*)c->Wn; T* WnT = (T*)c->WnT;
+  T* E = (T*)c->E; T* ET = (T*)c->ET;
+
+  PFC_LAUNCH(c, KID_NORM_X, normalize_x_kernel<T>, dim3((Bp + 3) / 4), dim3(256), 0, X, B, Bp, D,
+             yl, k, Xn, c->rnormX, c->clabel, c->err_flag);
+
+  constexpr int RPB = sizeof(T) == 2 ? 64 : 32;
+  const size_t gsm = (size_t)RPB * ((size_t)D * sizeof(T) + 4);
+  auto gather_kernel = gather_normalize_w_kernel<T, RPB>;
+  PFC_HIP(hipFuncSetAttribute((const void*)gather_kernel,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)gsm));
+  PFC_LAUNCH(c, KID_GATHER_W, gather_kernel, dim3((unsigned)(kp / RPB)),
+             dim3(256), gsm, W, c->N, idx, k, kp, D, Wn, WnT, c->rnormW, c->err_flag);
+
+  {
+    const int tiles_j = (int)(kp / CfgF::BM), tiles_i = Bp / CfgF::BN;
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgF>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
+    PFC_LAUNCH(c, KID_GEMM_LOGITS, gemm_logits_kernel<CfgF>, dim3(xcd_grid(tiles_i, tiles_j)),
+               dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, Bp, kp, yl, s, cos_m, sin_m,
+               E, ET, c->rowpart, c->clabel, tiles_j, tiles_i);
+    PFC_LAUNCH(c, KID_ROW_COMBINE, row_combine_kernel, dim3((Bp + 31) / 32), dim3(1024), 0,
+               c->rowpart, tiles_j, B, Bp, c->clabel, s, cos_m, sin_m, c->rowscale, c->dlabel,
+               c->lossrow);
+  }
+  PFC_LAUNCH(c, KID_LOSS_REDUCE, loss_reduce_kernel, dim3(1), dim3(256), 0, c->lossrow, B,
+             loss_out);
+  PFC_LAUNCH(c, KID_MAKE_XST, make_xst_kernel<T>, dim3(Bp / 32, D / 32), dim3(256), 0, X, B, Bp, D,
+             c->rnormX, c->rowscale, XsT);
+  {
+    const int tiles_j = (int)(kp / CfgW::BM), tiles_d = D / CfgW::BN;
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
+    PFC_LAUNCH(c, KID_GEMM_DW, gemm_dweight_kernel<CfgW>, dim3(xcd_grid(tiles_d, tiles_j)),
+               dim3(CfgW::THREADS), CfgW::LDS_BYTES, ET, XsT, D, k, Bp, dW_out, tiles_j, tiles_d);
+  }
+  PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel, dim3(B), dim3(128), 0, X, B, D, yl, k,
+             c->rnormX, c->dlabel, dW_out);
+  int splits;
+  {
+    const int tiles_i = Bp / CfgX::BM, tiles_d = D / CfgX::BN;
+    const int slabs_total = (int)(kp / CfgX::BK);
+    int want = 1024 / (tiles_i * tiles_d);
+    if (want < 1) want = 1;
+    if (want > kMaxSplits) want = kMaxSplits;
+    if (want > slabs_total) want = slabs_total;
+    const int slabs_per = (slabs_total + want - 1) / want;
+    splits = (slabs_total + slabs_per - 1) / slabs_per;
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dfeatures_kernel<CfgX>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgX::LDS_BYTES));
+    PFC_LAUNCH(c, KID_GEMM_DX, gemm_dfeatures_kernel<CfgX>,
+               dim3(xcd_grid(tiles_i * tiles_d, splits)), dim3(CfgX::THREADS), CfgX::LDS_BYTES, E,
+               WnT, D, Bp, kp, slabs_total, slabs_per, splits, c->dXpart, tiles_i, tiles_d);
+  }
+  PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel, dim3((B + 3) / 4), dim3(256), 0, c->dXpart,
+             splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW, c->rowscale,
+             c->dlabel, dX_out);
+  return PFC_OK;
+}
+
+}  // namespace
+
+int forward_backward_impl(pfc_ctx* c, const float* X, const float* W, const int32_t* idx,
+                          int64_t k, const int32_t* yl, int32_t B, float s, float m,
+                          float* loss_out, float* dX_out, float* dW_out) {
+  if (c->precision == PFC_PRECISION_BF16)
+    return run<__bf16>(c, X, W, idx, k, yl, B, s, m, loss_out, dX_out, dW_out);
+  return run<float>(c, X, W, idx, k, yl, B, s, m, loss_out, dX_out, dW_out);
+}
+
+}  // namespace pfc

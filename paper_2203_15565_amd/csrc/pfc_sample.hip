@@ -1,0 +1,402 @@
+// pfc_sample: the sampled class set S of one iteration (arXiv 2203.15565, Sec. 3.2 / Fig. 4:
+// the classes present in the batch go in first, random negatives fill the buffer up to r*N).
+//
+// Integer work only.  Every class gets a 32-bit Philox4x32-10 score (Salmon et al., SC'11),
+// recomputed wherever it is needed (about 60 integer operations per four classes; nothing is
+// stored per class except one "is in the batch" bit).  The k - U negatives with the largest
+// scores are found by a three-pass radix select (11 + 11 + 10 bits), equal scores going to the
+// smaller class id; an index-ordered compaction then writes S in ascending class id.
+#include <math.h>
+
+#include "pfc_common.h"
+
+namespace pfc {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kClassesPerBlock = 2048;                 // ordered passes: 2 x (256 threads x 4)
+constexpr int kItersPerBlock = kClassesPerBlock / (kThreads * 4);
+
+struct PhiloxKey {
+  uint32_t k0, k1;   // lo32(seed), hi32(seed)
+  uint32_t c2, c3;   // lo32(step), hi32(step)
+  uint32_t mask;     // ANDed onto every score
+};
+
+// Scores of classes 4q .. 4q+3.
+__device__ __forceinline__ void philox_block(uint32_t q, const PhiloxKey& key, uint32_t out[4]) {
+  uint32_t c0 = q, c1 = 0u, c2 = key.c2, c3 = key.c3;   // class ids are < 2^31, so hi32(j/4) = 0
+  uint32_t k0 = key.k0, k1 = key.k1;
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0;
+    const uint32_t n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0 & key.mask; out[1] = c1 & key.mask; out[2] = c2 & key.mask; out[3] = c3 & key.mask;
+}
+
+// The four "is positive" bits of classes 4q..4q+3 (bit e = class 4q+e).
+__device__ __forceinline__ uint32_t pos_nibble(const uint32_t* __restrict__ pos_bits, uint32_t q) {
+  return (pos_bits[q >> 3] >> ((q & 7u) * 4u)) & 0xFu;
+}
+
+__global__ void sample_init_kernel(uint32_t* __restrict__ pos_bits, int64_t nwords,
+                                   uint32_t* __restrict__ hist, SelState* __restrict__ sel) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = t; i < nwords; i += stride) pos_bits[i] = 0u;
+  for (int64_t i = t; i < 3 * 2048; i += stride) hist[i] = 0u;
+  if (t < (int64_t)(sizeof(SelState) / 4)) reinterpret_cast<uint32_t*>(sel)[t] = 0u;
+}
+
+__global__ void sample_mark_kernel(const int64_t* __restrict__ labels, int B, int64_t N,
+                                   uint32_t* __restrict__ pos_bits, int32_t* __restrict__ err_flag) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B) return;
+  const int64_t y = labels[i];
+  if (y < 0 || y >= N) {
+    atomicOr(err_flag, 1);
+    return;
+  }
+  atomicOr(&pos_bits[y >> 5], 1u << (y & 31));
+}
+
+// Radix pass P over the non-positive classes whose score agrees with the prefix found so far.
+// P = 0: bins = bits 31..21; also counts the positives.  P = 1: bits 20..10.  P = 2: bits 9..0.
+template <int P>
+__global__ void sample_hist_kernel(int64_t N, PhiloxKey key, const uint32_t* __restrict__ pos_bits,
+                                   uint32_t* __restrict__ hist, SelState* __restrict__ sel) {
+  __shared__ uint32_t lh[2048];
+  __shared__ uint32_t lpos;
+  for (int b = threadIdx.x; b < 2048; b += blockDim.x) lh[b] = 0u;
+  if (threadIdx.x == 0) lpos = 0u;
+  __syncthreads();
+  uint32_t prefix = 0u, none = 0u;
+  if (P > 0) {
+    prefix = sel->prefix;
+    none = sel->none;
+  }
+  if (!(P > 0 && none)) {
+    const uint32_t nq = (uint32_t)((N + 3) >> 2);
+    uint32_t npos = 0;
+    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < nq; q += gridDim.x * blockDim.x) {
+      uint32_t u[4];
+      philox_block(q, key, u);
+      const uint32_t pb = pos_nibble(pos_bits, q);
+      if (P == 0) npos += __popc(pb);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int64_t j = (int64_t)q * 4 + e;
+        if (j >= N || ((pb >> e) & 1u)) continue;
+        if (P == 0) {
+          atomicAdd(&lh[u[e] >> 21], 1u);
+        } else if (P == 1) {
+          if ((u[e] >> 21) == (prefix >> 21)) atomicAdd(&lh[(u[e] >> 10) & 2047u], 1u);
+        } else {
+          if ((u[e] >> 10) == (prefix >> 10)) atomicAdd(&lh[u[e] & 1023u], 1u);
+        }
+      }
+    }
+    if (P == 0 && npos) atomicAdd(&lpos, npos);
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < 2048; b += blockDim.x) {
+    const uint32_t c = lh[b];
+    if (c) atomicAdd(&hist[P * 2048 + b], c);
+  }
+  if (P == 0 && threadIdx.x == 0 && lpos) atomicAdd(&sel->U, lpos);
+}
+
+// One block of 256 threads: walk the histogram from the largest bin downwards until `need`
+// classes are covered; fix the bin as the next bits of the threshold.
+template <int P>
+__global__ void sample_scan_kernel(const uint32_t* __restrict__ hist, SelState* __restrict__ sel,
+                                   uint32_t ceil_rN) {
+  __shared__ uint32_t wsum[4];
+  __shared__ uint32_t s_need, s_none;
+  const int t = threadIdx.x;
+  if (t == 0) {
+    if (P == 0) {
+      const uint32_t U = sel->U;
+      const uint32_t k = U > ceil_rN ? U : ceil_rN;
+      sel->k = k;
+      s_need = k - U;
+      s_none = (k == U) ? 1u : 0u;
+      sel->none = s_none;
+    } else {
+      s_need = sel->need;
+      s_none = sel->none;
+    }
+  }
+  __syncthreads();
+  if (s_none) return;
+  const uint32_t need = s_need;
+  constexpr int kBins = (P == 2) ? 1024 : 2048;
+  constexpr int kPer = kBins / 256;
+  // thread t owns the descending bins kBins-1-t*kPer .. kBins-1-(t*kPer+kPer-1)
+  uint32_t mine = 0;
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) mine += hist[P * 2048 + (kBins - 1 - (t * kPer + e))];
+  // inclusive scan over threads
+  uint32_t inc = mine;
+  const int lane = t & 63, w = t >> 6;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t n = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += n;
+  }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int i = 0; i < w; ++i) base += wsum[i];
+  inc += base;
+  const uint32_t exc = inc - mine;
+  if (exc < need && need <= inc) {
+    uint32_t cum = exc;
+    for (int e = 0; e < kPer; ++e) {
+      const int b = kBins - 1 - (t * kPer + e);
+      const uint32_t c = hist[P * 2048 + b];
+      if (cum + c >= need) {
+        sel->need = need - cum;   // how many to take from inside this bin
+        const int shift = (P == 0) ? 21 : (P == 1) ? 10 : 0;
+        sel->prefix = sel->prefix | ((uint32_t)b << shift);
+        break;
+      }
+      cum += c;
+    }
+  }
+}
+
+// Selection predicate pieces for classes 4q..4q+3: bit e of `sure` = positive or score above the
+// threshold; bit e of `eq` = non-positive and score equal to the threshold.
+__device__ __forceinline__ void classify(uint32_t q, int64_t N, const PhiloxKey& key,
+                                         const uint32_t* __restrict__ pos_bits, uint32_t T,
+                                         uint32_t none, uint32_t& sure, uint32_t& eq) {
+  sure = 0u;
+  eq = 0u;
+  const uint32_t nq = (uint32_t)((N + 3) >> 2);
+  if (q >= nq) return;
+  uint32_t u[4];
+  philox_block(q, key, u);
+  const uint32_t pb = pos_nibble(pos_bits, q);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int64_t j = (int64_t)q * 4 + e;
+    if (j >= N) continue;
+    if ((pb >> e) & 1u) {
+      sure |= 1u << e;
+    } else if (!none) {
+      if (u[e] > T) sure |= 1u << e;
+      else if (u[e] == T) eq |= 1u << e;
+    }
+  }
+}
+
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* sm) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  const uint32_t r = sm[0] + sm[1] + sm[2] + sm[3];
+  __syncthreads();
+  return r;
+}
+
+// exclusive scan over the 256 threads of a block; also returns the block total
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t& total) {
+  uint32_t inc = v;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t n = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += n;
+  }
+  if (lane == 63) sm[w] = inc;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int i = 0; i < w; ++i) base += sm[i];
+  total = sm[0] + sm[1] + sm[2] + sm[3];
+  __syncthreads();
+  return base + inc - v;
+}
+
+__global__ void sample_count_kernel(int64_t N, PhiloxKey key, const uint32_t* __restrict__ pos_bits,
+                                    const SelState* __restrict__ sel, uint32_t* __restrict__ blk_cnt) {
+  __shared__ uint32_t sm[4];
+  const uint32_t T = sel->prefix, none = sel->none;
+  uint32_t nsure = 0, neq = 0;
+#pragma unroll
+  for (int it = 0; it < kItersPerBlock; ++it) {
+    const uint32_t q = blockIdx.x * (kClassesPerBlock / 4) + it * kThreads + threadIdx.x;
+    uint32_t sure, eq;
+    classify(q, N, key, pos_bits, T, none, sure, eq);
+    nsure += __popc(sure);
+    neq += __popc(eq);
+  }
+  const uint32_t bs = block_sum(nsure, sm);
+  const uint32_t be = block_sum(neq, sm);
+  if (threadIdx.x == 0) {
+    blk_cnt[2 * blockIdx.x] = bs;
+    blk_cnt[2 * blockIdx.x + 1] = be;
+  }
+}
+
+// One block: turn per-block counts into per-block output offsets.  A block takes its
+// equal-to-threshold classes only while the quota sel->need lasts (smaller ids first).
+__global__ void sample_blkscan_kernel(int nblk, const uint32_t* __restrict__ blk_cnt,
+                                      uint32_t* __restrict__ blk_off, SelState* __restrict__ sel) {
+  __shared__ uint32_t sm[4];
+  const uint32_t need_eq = sel->none ? 0u : sel->need;
+  uint32_t run_eq = 0, run_sel = 0;
+  for (int b0 = 0; b0 < nblk; b0 += kThreads) {
+    const int b = b0 + threadIdx.x;
+    const uint32_t cs = b < nblk ? blk_cnt[2 * b] : 0u;
+    const uint32_t ce = b < nblk ? blk_cnt[2 * b + 1] : 0u;
+    uint32_t tot_e, tot_s;
+    const uint32_t eq_before = run_eq + block_excl_scan(ce, sm, tot_e);
+    uint32_t take = 0;
+    if (eq_before < need_eq) {
+      take = need_eq - eq_before;
+      if (take > ce) take = ce;
+    }
+    const uint32_t off = run_sel + block_excl_scan(cs + take, sm, tot_s);
+    if (b < nblk) {
+      blk_off[2 * b] = off;
+      blk_off[2 * b + 1] = eq_before;
+    }
+    run_eq += tot_e;
+    run_sel += tot_s;
+  }
+  if (threadIdx.x == 0) sel->total = run_sel;
+}
+
+__global__ void sample_write_kernel(int64_t N, PhiloxKey key, const uint32_t* __restrict__ pos_bits,
+                                    const SelState* __restrict__ sel,
+                                    const uint32_t* __restrict__ blk_off, int64_t cap,
+                                    int32_t* __restrict__ idx_out) {
+  __shared__ uint32_t sm[4];
+  const uint32_t T = sel->prefix, none = sel->none;
+  const uint32_t need_eq = none ? 0u : sel->need;
+  uint32_t out = blk_off[2 * blockIdx.x];
+  uint32_t eq_run = blk_off[2 * blockIdx.x + 1];
+#pragma unroll
+  for (int it = 0; it < kItersPerBlock; ++it) {
+    const uint32_t q = blockIdx.x * (kClassesPerBlock / 4) + it * kThreads + threadIdx.x;
+    uint32_t sure, eq;
+    classify(q, N, key, pos_bits, T, none, sure, eq);
+    uint32_t tot_e, tot_s;
+    uint32_t eq_rank = eq_run + block_excl_scan(__popc(eq), sm, tot_e);
+    // keep an equal-score class only while the quota lasts (ascending class id)
+    uint32_t chosen = sure;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if ((eq >> e) & 1u) {
+        if (eq_rank < need_eq) chosen |= 1u << e;
+        ++eq_rank;
+      }
+    }
+    uint32_t pos = out + block_excl_scan(__popc(chosen), sm, tot_s);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if ((chosen >> e) & 1u) {
+        if ((int64_t)pos < cap) idx_out[pos] = (int32_t)(q * 4u + e);
+        ++pos;
+      }
+    }
+    eq_run += tot_e;
+    out += tot_s;
+  }
+}
+
+// labels_local[i] = position of labels[i] in the ascending idx (binary search), -1 if absent.
+__global__ void sample_remap_kernel(const int64_t* __restrict__ labels, int B, int64_t N,
+                                    const int32_t* __restrict__ idx, const SelState* __restrict__ sel,
+                                    int64_t cap, int32_t* __restrict__ yl_out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B) return;
+  const int64_t y = labels[i];
+  int64_t k = sel->total;
+  if (k > cap) k = cap;
+  int32_t res = -1;
+  if (y >= 0 && y < N) {
+    int64_t lo = 0, hi = k;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if (idx[mid] < (int32_t)y) lo = mid + 1; else hi = mid;
+    }
+    if (lo < k && idx[lo] == (int32_t)y) res = (int32_t)lo;
+  }
+  yl_out[i] = res;
+}
+
+}  // namespace
+
+int sample_impl(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t seed,
+                uint64_t step, uint32_t score_mask, int32_t* idx_out, int32_t* yl_out,
+                int64_t* k_out) {
+  const int64_t N = c->N;
+  int64_t crn = (int64_t)ceil(r * (double)N);
+  if (crn > N) crn = N;
+  if (crn < 1) crn = 1;
+  const int64_t cap = pfc_num_sampled(N, B, r);
+  PhiloxKey key;
+  key.k0 = (uint32_t)(seed & 0xFFFFFFFFu);
+  key.k1 = (uint32_t)(seed >> 32);
+  key.c2 = (uint32_t)(step & 0xFFFFFFFFu);
+  key.c3 = (uint32_t)(step >> 32);
+  key.mask = score_mask;
+
+  const int64_t nwords = (N + 31) / 32 + 1;
+  const int nblk = (int)((N + kClassesPerBlock - 1) / kClassesPerBlock);
+  if (nblk > c->nblk_cap) return PFC_EINVAL;
+  const int64_t nq = (N + 3) / 4;
+  int hist_blocks = (int)((nq + kThreads * 4 - 1) / (kThreads * 4));
+  if (hist_blocks > 2048) hist_blocks = 2048;
+  if (hist_blocks < 1) hist_blocks = 1;
+  int init_blocks = (int)((nwords + kThreads - 1) / kThreads);
+  if (init_blocks > 1024) init_blocks = 1024;
+  if (init_blocks < 24) init_blocks = 24;   // also covers the 3 x 2048 histogram words
+
+  PFC_LAUNCH(c, KID_SAMPLE_INIT, sample_init_kernel, dim3(init_blocks), dim3(kThreads), 0,
+             c->pos_bits, nwords, c->hist, c->sel);
+  PFC_LAUNCH(c, KID_SAMPLE_MARK, sample_mark_kernel, dim3((B + kThreads - 1) / kThreads),
+             dim3(kThreads), 0, labels, B, N, c->pos_bits, c->err_flag);
+  PFC_LAUNCH(c, KID_SAMPLE_HIST0, sample_hist_kernel<0>, dim3(hist_blocks), dim3(kThreads), 0, N,
+             key, c->pos_bits, c->hist, c->sel);
+  PFC_LAUNCH(c, KID_SAMPLE_SCAN0, sample_scan_kernel<0>, dim3(1), dim3(kThreads), 0, c->hist,
+             c->sel, (uint32_t)crn);
+  PFC_LAUNCH(c, KID_SAMPLE_HIST1, sample_hist_kernel<1>, dim3(hist_blocks), dim3(kThreads), 0, N,
+             key, c->pos_bits, c->hist, c->sel);
+  PFC_LAUNCH(c, KID_SAMPLE_SCAN1, sample_scan_kernel<1>, dim3(1), dim3(kThreads), 0, c->hist,
+             c->sel, (uint32_t)crn);
+  PFC_LAUNCH(c, KID_SAMPLE_HIST2, sample_hist_kernel<2>, dim3(hist_blocks), dim3(kThreads), 0, N,
+             key, c->pos_bits, c->hist, c->sel);
+  PFC_LAUNCH(c, KID_SAMPLE_SCAN2, sample_scan_kernel<2>, dim3(1), dim3(kThreads), 0, c->hist,
+             c->sel, (uint32_t)crn);
+  PFC_LAUNCH(c, KID_SAMPLE_COUNT, sample_count_kernel, dim3(nblk), dim3(kThreads), 0, N, key,
+             c->pos_bits, c->sel, c->blk_cnt);
+  PFC_LAUNCH(c, KID_SAMPLE_BLKSCAN, sample_blkscan_kernel, dim3(1), dim3(kThreads), 0, nblk,
+             c->blk_cnt, c->blk_off, c->sel);
+  PFC_LAUNCH(c, KID_SAMPLE_WRITE, sample_write_kernel, dim3(nblk), dim3(kThreads), 0, N, key,
+             c->pos_bits, c->sel, c->blk_off, cap, idx_out);
+  PFC_LAUNCH(c, KID_SAMPLE_REMAP, sample_remap_kernel, dim3((B + kThreads - 1) / kThreads),
+             dim3(kThreads), 0, labels, B, N, idx_out, c->sel, cap, yl_out);
+
+  if (crn >= (int64_t)B) {
+    // U <= B <= ceil(r*N): k is known without the labels.
+    *k_out = crn;
+  } else {
+    PFC_HIP(hipMemcpyAsync(c->host_pin, &c->sel->k, 4, hipMemcpyDeviceToHost, c->stream));
+    PFC_HIP(hipStreamSynchronize(c->stream));
+    *k_out = (int64_t)c->host_pin[0];
+  }
+  return PFC_OK;
+}
+
+}  // namespace pfc

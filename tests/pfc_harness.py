@@ -1,0 +1,59 @@
+"""Helpers shared by the GPU parity tests: run the HIP path through the C ABI and the oracle on
+the same seeded inputs.  Nothing here computes any part of the method."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import pfc_oracle as O
+from paper_2203_15565_amd import binding
+
+
+def torch_mod():
+    import torch
+    return torch
+
+
+def gpu_sample(ctx, labels_np, r, seed, step, score_mask=None):
+    """Returns (idx int32[k], y_local int32[B], k) as NumPy arrays from pfc_sample."""
+    torch = torch_mod()
+    B = labels_np.size
+    cap = binding.pfc_num_sampled(ctx.N, B, r)
+    labels = torch.from_numpy(np.ascontiguousarray(labels_np, dtype=np.int64)).cuda()
+    idx = torch.full((cap,), -7, dtype=torch.int32, device="cuda")
+    yl = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    k = ctx.pfc_sample(labels, r, seed, step, idx, yl, score_mask=score_mask)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), yl.cpu().numpy(), k
+
+
+def gpu_forward_backward(ctx, X_np, W_dev, idx_np, yl_np, s, m):
+    """W_dev: torch fp32 [N x D] on the GPU.  Returns (loss, dX, dWn) as NumPy."""
+    torch = torch_mod()
+    B, D = X_np.shape
+    k = idx_np.size
+    X = torch.from_numpy(np.ascontiguousarray(X_np, dtype=np.float32)).cuda()
+    idx = torch.from_numpy(np.ascontiguousarray(idx_np, dtype=np.int32)).cuda()
+    yl = torch.from_numpy(np.ascontiguousarray(yl_np, dtype=np.int32)).cuda()
+    loss = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    dX = torch.full((B, D), float("nan"), dtype=torch.float32, device="cuda")
+    dW = torch.full((k, D), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.pfc_forward_backward(X, W_dev, idx, k, yl, s, m, loss, dX, dW)
+    torch.cuda.synchronize()
+    return float(loss.item()), dX.cpu().numpy(), dW.cpu().numpy()
+
+
+def rel_max(a, b):
+    """max |a-b| / max |b|"""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-300))
+
+
+def row_rel_err(W_gpu, W_ref, ref_norm):
+    """max over rows of max|row diff| / |reference row|  (the bar for updated centers)."""
+    d = np.abs(np.asarray(W_gpu, dtype=np.float64) - np.asarray(W_ref, dtype=np.float64)).max(axis=1)
+    return float((d / ref_norm).max())
+
+
+def oracle_step(X, labels, W64, v64, wl_kwargs):
+    return O.step(X, labels, W64, v64, **wl_kwargs)
