@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of one Partial FC training step (sample + forward/backward + update) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline] [--no-cpu-baseline]
+
+Prints ONE JSON line: whole-step throughput in samples/s with all inputs resident in HBM, the
+roofline of the dominant kernel (measured with HIP events on the library's stream) and the fp64
+CPU oracle timed on the same workload as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, GB/s
+PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA
+PEAK_FP32_MFMA_TFLOPS = 157.3  # fp32 MFMA
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
+# (workload, kernel).  None where no counter run has been recorded.
+MEASURED_TRAFFIC_BYTES: dict = {}
+
+
+def algorithmic_work(B: int, D: int, k: int, precision: int) -> dict:
+    """Algorithmic flops / HBM bytes of the main kernels for one step (what the method must
+    compute or move, not what this implementation adds)."""
+    es = 2 if precision == 1 else 4
+    gemm = 2.0 * B * D * k
+    return {
+        "gemm_logits": ("mfma", gemm),
+        "gemm_dweight": ("mfma", gemm),
+        "gemm_dfeatures": ("mfma", gemm),
+        "gather_normalize_w": ("hbm", k * D * (4 + es) + 4.0 * k),
+        "update": ("hbm", 5.0 * k * D * 4),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="headline")
+    ap.add_argument("--r", type=float, default=None, help="override the sampling ratio")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2203_15565_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    wl = workloads.CONFIGS[args.workload]
+    if args.r is not None:
+        wl = wl.with_(r=args.r)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, Wm = args.steps, args.warmup
+    nsteps = K + Wm
+
+    # ---- inputs, resident in HBM before anything is timed --------------------------------
+    Wd = torch.empty((wl.N, wl.D), dtype=torch.float32, device=dev)
+    for row0, chunk in workloads.weight_chunks(wl):
+        Wd[row0:row0 + chunk.shape[0]].copy_(torch.from_numpy(chunk))
+    vd = torch.zeros_like(Wd)
+    feats = [torch.from_numpy(workloads.make_features(wl, t)).to(dev) for t in range(nsteps)]
+    labels_np = [workloads.make_labels(wl, t) for t in range(nsteps)]
+    labels = [torch.from_numpy(l).to(dev) for l in labels_np]
+
+    ctx = binding.Context(wl.N, wl.D, wl.B, wl.r, wl.precision)
+    cap = binding.pfc_num_sampled(wl.N, wl.B, wl.r)
+    idx = torch.zeros(cap, dtype=torch.int32, device=dev)
+    yl = torch.zeros(wl.B, dtype=torch.int32, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    dX = torch.zeros((wl.B, wl.D), dtype=torch.float32, device=dev)
+    dW = torch.zeros((cap, wl.D), dtype=torch.float32, device=dev)
+
+    def step(t: int) -> int:
+        k = ctx.pfc_sample(labels[t], wl.r, wl.seed, t, idx, yl)
+        ctx.pfc_forward_backward(feats[t], Wd, idx, k, yl, wl.s, wl.m, loss, dX, dW)
+        ctx.pfc_update(Wd, vd, idx, k, dW, wl.lr, wl.mu)
+        return k
+
+    # ---- cpu baseline: the oracle, one whole step on the same inputs (state before any step) --
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import pfc_oracle as O
+        t0 = time.perf_counter()
+        oidx, oyl, ok = O.sample(labels_np[0], wl.N, wl.r, wl.seed, 0)
+        t_sample = time.perf_counter() - t0
+        sel = torch.from_numpy(oidx.astype(np.int64)).to(dev)
+        W_S = Wd[sel].cpu().numpy()
+        v_S = np.zeros_like(W_S, dtype=np.float64)
+        X0 = feats[0].cpu().numpy()
+        t0 = time.perf_counter()
+        fb = O.forward_backward(X0, W_S, oyl, wl.s, wl.m)
+        W_S64 = W_S.astype(np.float64)
+        O.update(W_S64, v_S, np.arange(ok), fb["dW"], wl.lr, wl.mu)
+        t_rest = time.perf_counter() - t0
+        t_oracle = t_sample + t_rest
+        try:
+            import threadpoolctl
+            cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        cpu_baseline = {
+            "value": wl.B / t_oracle, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": "1 whole step of the %s workload (B=%d, k=%d) in NumPy fp64: sampling %.2f s, "
+                      "loss+gradients+update %.2f s" % (wl.name, wl.B, ok, t_sample, t_rest),
+            "oracle_loss": fb["loss"],
+        }
+        del fb, W_S, W_S64, v_S
+
+    # ---- warm-up, then the timed region ---------------------------------------------------
+    k = 0
+    for t in range(Wm):
+        k = step(t)
+    torch.cuda.synchronize()
+    if ctx.pfc_check() != binding.PFC_OK:
+        print("bench.py: device reported an out-of-range label", file=sys.stderr)
+        return 1
+    first_loss = None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(Wm, nsteps):
+        k = step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / K * 1e3
+    value = wl.B * K / elapsed
+
+    # ---- per-kernel durations: same steps again with an event pair around every kernel ----
+    ctx.pfc_set_timing(True)
+    acc: dict = {}
+    reps = min(K, 10)
+    for t in range(reps):
+        step(Wm + t)
+        for name, ms in ctx.pfc_get_timing().items():
+            acc.setdefault(name, []).append(ms)
+    ctx.pfc_set_timing(False)
+    kern_ms = {n: float(np.mean(v)) for n, v in acc.items()}
+    work = algorithmic_work(wl.B, wl.D, k, wl.precision)
+    peak_mfma = PEAK_BF16_TFLOPS if wl.precision == 1 else PEAK_FP32_MFMA_TFLOPS
+    kernels = {}
+    for name, ms in sorted(kern_ms.items(), key=lambda kv: -kv[1]):
+        ent = {"ms": round(ms, 5)}
+        if name in work:
+            bound, amount = work[name]
+            if bound == "mfma":
+                ach = amount / (ms * 1e-3) / 1e12
+                ent.update(bound="mfma", achieved=round(ach, 2), peak=peak_mfma, unit="TFLOP/s",
+                           frac=round(ach / peak_mfma, 4))
+            else:
+                ach = amount / (ms * 1e-3) / 1e9
+                ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                           frac=round(ach / PEAK_HBM_GBS, 4))
+        kernels[name] = ent
+    dominant = max((n for n in kern_ms if n in work), key=lambda n: kern_ms[n])
+    roofline = {"kernel": dominant}
+    roofline.update({f: kernels[dominant][f] for f in ("bound", "achieved", "peak", "unit", "frac")})
+    roofline["ms"] = kernels[dominant]["ms"]
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant))
+
+    if cpu_baseline is not None:
+        # parity spot check of the run itself: loss of step 0 from a fresh state is not
+        # available any more (state has advanced); the tests cover parity.  Report only.
+        pass
+
+    out = {
+        "metric": "PFC fwd+bwd+update samples/s",
+        "value": round(value, 1),
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.precision == 1 else "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: B=%d D=%d N=%d r=%g k=%d, Zipf(%.1f) labels, s=%g m=%g, "
+                               "SGD lr=%g mu=%g" % (wl.name, wl.B, wl.D, wl.N, wl.r, k,
+                                                    wl.zipf_alpha, wl.s, wl.m, wl.lr, wl.mu),
+                   "B": wl.B, "D": wl.D, "N": wl.N, "r": wl.r, "k": k},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "kernels": kernels,
+        "kernel_sum_ms": round(sum(kern_ms.values()), 4),
+        "final_loss": float(loss.item()),
+    }
+    print(json.dumps(out))
+    ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -62,14 +62,13 @@ __device__ __forceinline__ void mfma_group<__bf16>(const u32x4& a, const u32x4& 
 
 template <>
 __device__ __forceinline__ void mfma_group<float>(const u32x4& a, const u32x4& b, f32x16& c) {
-  c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.x),
-                                           __builtin_bit_cast(float, b.x), c, 0, 0, 0);
-  c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.y),
-                                           __builtin_bit_cast(float, b.y), c, 0, 0, 0);
-  c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.z),
-                                           __builtin_bit_cast(float, b.z), c, 0, 0, 0);
-  c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.w),
-                                           __builtin_bit_cast(float, b.w), c, 0, 0, 0);
+  // whole-vector casts: a bit_cast applied to a single vector element reads element 0
+  const f32x4 af = __builtin_bit_cast(f32x4, a);
+  const f32x4 bf = __builtin_bit_cast(f32x4, b);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[0], bf[0], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[1], bf[1], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[2], bf[2], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[3], bf[3], c, 0, 0, 0);
 }
 
 // Accumulate acc += A_tile * B_tile^T over `nslabs` slabs of K.

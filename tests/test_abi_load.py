@@ -67,3 +67,14 @@ def test_null_context_is_einval():
     assert lib.pfc_update(None, None, None, None, 1, None, 0.1, 0.9) == binding.PFC_EINVAL
     assert lib.pfc_check(None) == binding.PFC_EINVAL
     assert lib.pfc_destroy(None) == binding.PFC_EINVAL
+
+
+def test_library_is_not_older_than_its_sources():
+    """Guards against running GPU tests on a stale build: rebuild after touching csrc/."""
+    if not os.path.exists(binding.LIB_PATH):
+        pytest.skip("libpfc.so not built")
+    lib_m = os.path.getmtime(binding.LIB_PATH)
+    csrc = os.path.join(ROOT, "paper_2203_15565_amd", "csrc")
+    srcs = [os.path.join(csrc, f) for f in os.listdir(csrc)] + [os.path.join(ROOT, "include", "pfc.h")]
+    newest = max(os.path.getmtime(p) for p in srcs)
+    assert lib_m >= newest, "libpfc.so is older than its sources: run python -m paper_2203_15565_amd.build"

@@ -169,9 +169,10 @@ def _run_steps(wl, nsteps, check_every_step=True):
         X = workloads.make_features(wl, t)
         labels = workloads.make_labels(wl, t)
         _say("step", wl.name, t)
-        k = ctx.pfc_sample(torch.from_numpy(labels).cuda(), wl.r, wl.seed, t, idx_d, yl_d)
-        ctx.pfc_forward_backward(torch.from_numpy(X).cuda(), Wd, idx_d, k, yl_d, wl.s, wl.m,
-                                 loss_d, dX_d, dW_d)
+        labels_d = torch.from_numpy(labels).cuda()      # referenced until the synchronize below
+        X_d = torch.from_numpy(X).cuda()
+        k = ctx.pfc_sample(labels_d, wl.r, wl.seed, t, idx_d, yl_d)
+        ctx.pfc_forward_backward(X_d, Wd, idx_d, k, yl_d, wl.s, wl.m, loss_d, dX_d, dW_d)
         ctx.pfc_update(Wd, vd, idx_d, k, dW_d, wl.lr, wl.mu)
         torch.cuda.synchronize()
         assert ctx.pfc_check() == binding.PFC_OK
