@@ -34,7 +34,7 @@ constexpr float kEpsSin2 = 1e-12f;
 // ---------------------------------------------------------------------------------------------
 // normalize_x: one wavefront per (padded) feature row.
 // ---------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int NC>
 __global__ void normalize_x_kernel(const float* __restrict__ X, int B, int Bp, int D,
                                    const int32_t* __restrict__ yl, int64_t k, T* __restrict__ Xn,
                                    float* __restrict__ rnormX, float* __restrict__ clabel,
@@ -42,10 +42,11 @@ __global__ void normalize_x_kernel(const float* __restrict__ X, int B, int Bp, i
   const int lane = threadIdx.x & 63;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (i >= Bp) return;
-  const int nchunk = D >> 8;   // float4 chunks per lane
-  float4 v[4];
+  constexpr int nchunk = NC;   // float4 chunks per lane (D = 256 * NC)
+  float4 v[NC];
   float ss = 0.f;
   if (i < B) {
+#pragma unroll
     for (int c = 0; c < nchunk; ++c) {
       v[c] = *reinterpret_cast<const float4*>(X + (int64_t)i * D + c * 256 + lane * 4);
       ss += v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
@@ -53,6 +54,7 @@ __global__ void normalize_x_kernel(const float* __restrict__ X, int B, int Bp, i
   }
   ss = wave_sum(ss);
   const float rn = (i < B) ? 1.f / fmaxf(sqrtf(ss), kEpsNorm) : 0.f;
+#pragma unroll
   for (int c = 0; c < nchunk; ++c) {
     T* dst = Xn + (int64_t)i * D + c * 256 + lane * 4;
     if (i < B) {
@@ -80,7 +82,7 @@ __global__ void normalize_x_kernel(const float* __restrict__ X, int B, int Bp, i
 // LDS tile; the block then writes the tile transposed into WnT so that every store instruction
 // covers whole 128-byte segments.  Rows k..kp-1 are written as zeros.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int RPB>
+template <typename T, int RPB, int NC>
 __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N,
                                           const int32_t* __restrict__ idx, int64_t k, int64_t kp,
                                           int D, T* __restrict__ Wn, T* __restrict__ WnT,
@@ -90,50 +92,65 @@ __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t j0 = (int64_t)blockIdx.x * RPB;
   const int rowbytes = D * (int)sizeof(T) + 4;   // +4: transposed reads then spread over banks
-  const int nchunk = D >> 8;
-  for (int rr = wave; rr < RPB; rr += 4) {
-    const int64_t j = j0 + rr;
-    float4 v[4];
-    float ss = 0.f;
-    bool ok = false;
-    if (j < k) {
-      const int64_t row = idx[j];
-      ok = (row >= 0 && row < N);
-      if (!ok && lane == 0) atomicOr(err_flag, 4);
-      if (ok) {
-        for (int c = 0; c < nchunk; ++c) {
-          v[c] = *reinterpret_cast<const float4*>(W + row * D + c * 256 + lane * 4);
-          ss += v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
+  constexpr int nchunk = NC;
+  constexpr int NB = 4;   // rows in flight per wavefront (memory-level parallelism)
+  for (int rb = wave * NB; rb < RPB; rb += 4 * NB) {
+    float4 v[NB][NC];
+    bool ok[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int64_t j = j0 + rb + u;
+      ok[u] = false;
+      if (j < k) {
+        const int64_t row = idx[j];
+        ok[u] = (row >= 0 && row < N);
+        if (!ok[u] && lane == 0) atomicOr(err_flag, 4);
+        if (ok[u]) {
+#pragma unroll
+          for (int c = 0; c < nchunk; ++c)
+            v[u][c] = *reinterpret_cast<const float4*>(W + row * D + c * 256 + lane * 4);
         }
       }
     }
-    ss = wave_sum(ss);
-    const float rn = ok ? 1.f / fmaxf(sqrtf(ss), kEpsNorm) : 0.f;
-    if (lane == 0) rnormW[j] = rn;
-    for (int c = 0; c < nchunk; ++c) {
-      T o[4];
-      if (ok) {
-        o[0] = from_float<T>(v[c].x * rn);
-        o[1] = from_float<T>(v[c].y * rn);
-        o[2] = from_float<T>(v[c].z * rn);
-        o[3] = from_float<T>(v[c].w * rn);
-      } else {
-        o[0] = o[1] = o[2] = o[3] = from_float<T>(0.f);
-      }
-      const int d = c * 256 + lane * 4;
-      T* g = Wn + j * D + d;
-      T* sdst = reinterpret_cast<T*>(smem + rr * rowbytes) + d;
-      if constexpr (sizeof(T) == 2) {
-        uint2 pk;
-        __builtin_memcpy(&pk, o, 8);
-        *reinterpret_cast<uint2*>(g) = pk;
-        reinterpret_cast<uint32_t*>(sdst)[0] = pk.x;   // LDS rows are only 4-byte aligned
-        reinterpret_cast<uint32_t*>(sdst)[1] = pk.y;
-      } else {
-        float4 f4;
-        f4.x = (float)o[0]; f4.y = (float)o[1]; f4.z = (float)o[2]; f4.w = (float)o[3];
-        *reinterpret_cast<float4*>(g) = f4;
-        sdst[0] = o[0]; sdst[1] = o[1]; sdst[2] = o[2]; sdst[3] = o[3];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int rr = rb + u;
+      const int64_t j = j0 + rr;
+      float ss = 0.f;
+      if (ok[u])
+#pragma unroll
+        for (int c = 0; c < nchunk; ++c)
+          ss += v[u][c].x * v[u][c].x + v[u][c].y * v[u][c].y + v[u][c].z * v[u][c].z +
+                v[u][c].w * v[u][c].w;
+      ss = wave_sum(ss);
+      const float rn = ok[u] ? 1.f / fmaxf(sqrtf(ss), kEpsNorm) : 0.f;
+      if (lane == 0) rnormW[j] = rn;
+#pragma unroll
+      for (int c = 0; c < nchunk; ++c) {
+        T o[4];
+        if (ok[u]) {
+          o[0] = from_float<T>(v[u][c].x * rn);
+          o[1] = from_float<T>(v[u][c].y * rn);
+          o[2] = from_float<T>(v[u][c].z * rn);
+          o[3] = from_float<T>(v[u][c].w * rn);
+        } else {
+          o[0] = o[1] = o[2] = o[3] = from_float<T>(0.f);
+        }
+        const int d = c * 256 + lane * 4;
+        T* g = Wn + j * D + d;
+        T* sdst = reinterpret_cast<T*>(smem + rr * rowbytes) + d;
+        if constexpr (sizeof(T) == 2) {
+          uint2 pk;
+          __builtin_memcpy(&pk, o, 8);
+          *reinterpret_cast<uint2*>(g) = pk;
+          reinterpret_cast<uint32_t*>(sdst)[0] = pk.x;   // LDS rows are only 4-byte aligned
+          reinterpret_cast<uint32_t*>(sdst)[1] = pk.y;
+        } else {
+          float4 f4;
+          f4.x = (float)o[0]; f4.y = (float)o[1]; f4.z = (float)o[2]; f4.w = (float)o[3];
+          *reinterpret_cast<float4*>(g) = f4;
+          sdst[0] = o[0]; sdst[1] = o[1]; sdst[2] = o[2]; sdst[3] = o[3];
+        }
       }
     }
   }
@@ -347,27 +364,82 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_kernel(
     }
 }
 
-// dweight_label: dWn[y] += sum over samples i with label y of dlabel_i * xn_i, in ascending i.
-// Block i does the whole sum for its class if i is the first sample carrying that label.
-__global__ void dweight_label_kernel(const float* __restrict__ X, int B, int D,
-                                     const int32_t* __restrict__ yl, int64_t k,
-                                     const float* __restrict__ rnormX,
-                                     const float* __restrict__ dlabel, float* __restrict__ dW) {
-  const int i = blockIdx.x;
+// dweight_label: dWn[y] += sum over samples i with label y of dlabel_i * xn_i.
+// Block i does the whole sum for its class if i is the first sample carrying that label.  The
+// matching samples are listed in ascending order; thread group g (one float4 column per thread)
+// sums the matches whose ordinal is congruent to g, and the groups are combined in fixed order,
+// so the result does not depend on timing.
+constexpr int kLabelThreads = 1024;
+__global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
+    const float* __restrict__ X, int B, int D, const int32_t* __restrict__ yl, int64_t k,
+    const float* __restrict__ rnormX, const float* __restrict__ dlabel, float* __restrict__ dW) {
+  __shared__ int s_list[kLabelThreads];
+  __shared__ int s_wcnt[kLabelThreads / 64];
+  __shared__ float4 s_part[kLabelThreads];
+  const int i = blockIdx.x, t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
   const int32_t y = yl[i];
   if (y < 0 || (int64_t)y >= k) return;
   int seen = 0;
-  for (int p = threadIdx.x; p < i; p += blockDim.x) seen |= (yl[p] == y);
+  for (int p = t; p < i; p += kLabelThreads) seen |= (yl[p] == y);
   if (__syncthreads_or(seen)) return;
-  float acc[8];
-  const int nc = D / 128;
-  for (int c = 0; c < nc; ++c) acc[c] = 0.f;
-  for (int p = i; p < B; ++p) {
-    if (yl[p] != y) continue;
-    const float a = dlabel[p] * rnormX[p];
-    for (int c = 0; c < nc; ++c) acc[c] += a * X[(int64_t)p * D + c * 128 + threadIdx.x];
+  const int cols = D >> 2;                 // float4 columns: 64 .. 256
+  const int G = kLabelThreads / cols;      // thread groups
+  const int col = t % cols, g = t / cols;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  int ordinal0 = 0;                        // matches seen in earlier chunks
+  for (int p0 = i; p0 < B; p0 += kLabelThreads) {
+    const int p = p0 + t;
+    const bool hit = (p < B) && (yl[p] == y);
+    const unsigned long long bal = __ballot(hit);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) s_wcnt[wave] = __popcll(bal);
+    __syncthreads();
+    int base = 0, total = 0;
+    for (int w = 0; w < kLabelThreads / 64; ++w) {
+      const int c = s_wcnt[w];
+      if (w < wave) base += c;
+      total += c;
+    }
+    if (hit) s_list[base + before] = p;
+    __syncthreads();
+    // group g takes list entries whose global ordinal is congruent to g modulo G
+    int e = (g - ordinal0 % G + G) % G;
+    for (; e + 3 * G < total; e += 4 * G) {
+      const int q0 = s_list[e], q1 = s_list[e + G], q2 = s_list[e + 2 * G], q3 = s_list[e + 3 * G];
+      const float4 x0 = *reinterpret_cast<const float4*>(X + (int64_t)q0 * D + col * 4);
+      const float4 x1 = *reinterpret_cast<const float4*>(X + (int64_t)q1 * D + col * 4);
+      const float4 x2 = *reinterpret_cast<const float4*>(X + (int64_t)q2 * D + col * 4);
+      const float4 x3 = *reinterpret_cast<const float4*>(X + (int64_t)q3 * D + col * 4);
+      const float a0 = dlabel[q0] * rnormX[q0], a1 = dlabel[q1] * rnormX[q1];
+      const float a2 = dlabel[q2] * rnormX[q2], a3 = dlabel[q3] * rnormX[q3];
+      acc.x += a0 * x0.x; acc.y += a0 * x0.y; acc.z += a0 * x0.z; acc.w += a0 * x0.w;
+      acc.x += a1 * x1.x; acc.y += a1 * x1.y; acc.z += a1 * x1.z; acc.w += a1 * x1.w;
+      acc.x += a2 * x2.x; acc.y += a2 * x2.y; acc.z += a2 * x2.z; acc.w += a2 * x2.w;
+      acc.x += a3 * x3.x; acc.y += a3 * x3.y; acc.z += a3 * x3.z; acc.w += a3 * x3.w;
+    }
+    for (; e < total; e += G) {
+      const int q = s_list[e];
+      const float4 x = *reinterpret_cast<const float4*>(X + (int64_t)q * D + col * 4);
+      const float a = dlabel[q] * rnormX[q];
+      acc.x += a * x.x; acc.y += a * x.y; acc.z += a * x.z; acc.w += a * x.w;
+    }
+    ordinal0 += total;
+    __syncthreads();
   }
-  for (int c = 0; c < nc; ++c) dW[(int64_t)y * D + c * 128 + threadIdx.x] += acc[c];
+  s_part[t] = acc;
+  __syncthreads();
+  if (g == 0) {
+    float4 r = s_part[col];
+    for (int gg = 1; gg < G; ++gg) {
+      const float4 o = s_part[gg * cols + col];
+      r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w;
+    }
+    float4* dst = reinterpret_cast<float4*>(dW + (int64_t)y * D + col * 4);
+    float4 cur = *dst;
+    cur.x += r.x; cur.y += r.y; cur.z += r.z; cur.w += r.w;
+    *dst = cur;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -411,6 +483,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_dfeatures_kernel(
 // dfeatures_final: one wavefront per sample.
 //   g  = (s/(B l_i)) * sum_slices part + dlabel_i * wn_{y_i}        (dL/d xn_i)
 //   dx = (g - <g, xn_i> xn_i) / |x_i|
+template <int NC>
 __global__ void dfeatures_final_kernel(const float* __restrict__ part, int splits, int B, int Bp,
                                        int D, const float* __restrict__ X,
                                        const float* __restrict__ W, int64_t N,
@@ -423,7 +496,7 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
   const int lane = threadIdx.x & 63;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (i >= B) return;
-  const int nchunk = D >> 8;
+  constexpr int nchunk = NC;
   const float rs = rowscale[i], rnx = rnormX[i], dl = dlabel[i];
   const int32_t y = yl[i];
   int64_t wrow = -1;
@@ -433,8 +506,9 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
     rnw = rnormW[y];
     if (wrow < 0 || wrow >= N) wrow = -1;
   }
-  float4 g[4], xn[4];
+  float4 g[NC], xn[NC];
   float u = 0.f;
+#pragma unroll
   for (int c = 0; c < nchunk; ++c) {
     const int d = c * 256 + lane * 4;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -455,6 +529,7 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
     u += a.x * x.x + a.y * x.y + a.z * x.z + a.w * x.w;
   }
   u = wave_sum(u);
+#pragma unroll
   for (int c = 0; c < nchunk; ++c) {
     float4 o;
     o.x = (g[c].x - u * xn[c].x) * rnx;
@@ -468,7 +543,7 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int NC>
 int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t k,
         const int32_t* yl, int32_t B, float s, float m, float* loss_out, float* dX_out,
         float* dW_out) {
@@ -482,12 +557,13 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   T* Xn = (T*)c->Xn; T* XsT = (T*)c->XsT; T* Wn = (T*)c->Wn; T* WnT = (T*)c->WnT;
   T* E = (T*)c->E; T* ET = (T*)c->ET;
 
-  PFC_LAUNCH(c, KID_NORM_X, normalize_x_kernel<T>, dim3((Bp + 3) / 4), dim3(256), 0, X, B, Bp, D,
+  auto norm_kernel = normalize_x_kernel<T, NC>;
+  PFC_LAUNCH(c, KID_NORM_X, norm_kernel, dim3((Bp + 3) / 4), dim3(256), 0, X, B, Bp, D,
              yl, k, Xn, c->rnormX, c->clabel, c->err_flag);
 
   constexpr int RPB = sizeof(T) == 2 ? 64 : 32;
   const size_t gsm = (size_t)RPB * ((size_t)D * sizeof(T) + 4);
-  auto gather_kernel = gather_normalize_w_kernel<T, RPB>;
+  auto gather_kernel = gather_normalize_w_kernel<T, RPB, NC>;
   PFC_HIP(hipFuncSetAttribute((const void*)gather_kernel,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gsm));
   PFC_LAUNCH(c, KID_GATHER_W, gather_kernel, dim3((unsigned)(kp / RPB)),
@@ -515,7 +591,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     PFC_LAUNCH(c, KID_GEMM_DW, gemm_dweight_kernel<CfgW>, dim3(xcd_grid(tiles_d, tiles_j)),
                dim3(CfgW::THREADS), CfgW::LDS_BYTES, ET, XsT, D, k, Bp, dW_out, tiles_j, tiles_d);
   }
-  PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel, dim3(B), dim3(128), 0, X, B, D, yl, k,
+  PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel, dim3(B), dim3(kLabelThreads), 0, X, B, D, yl, k,
              c->rnormX, c->dlabel, dW_out);
   int splits;
   {
@@ -533,7 +609,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                dim3(xcd_grid(tiles_i * tiles_d, splits)), dim3(CfgX::THREADS), CfgX::LDS_BYTES, E,
                WnT, D, Bp, kp, slabs_total, slabs_per, splits, c->dXpart, tiles_i, tiles_d);
   }
-  PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel, dim3((B + 3) / 4), dim3(256), 0, c->dXpart,
+  PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3((B + 3) / 4), dim3(256), 0, c->dXpart,
              splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW, c->rowscale,
              c->dlabel, dX_out);
   return PFC_OK;
@@ -544,9 +620,25 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
 int forward_backward_impl(pfc_ctx* c, const float* X, const float* W, const int32_t* idx,
                           int64_t k, const int32_t* yl, int32_t B, float s, float m,
                           float* loss_out, float* dX_out, float* dW_out) {
-  if (c->precision == PFC_PRECISION_BF16)
-    return run<__bf16>(c, X, W, idx, k, yl, B, s, m, loss_out, dX_out, dW_out);
-  return run<float>(c, X, W, idx, k, yl, B, s, m, loss_out, dX_out, dW_out);
+#define PFC_RUN(T, NC) return run<T, NC>(c, X, W, idx, k, yl, B, s, m, loss_out, dX_out, dW_out)
+  const int nc = c->D / 256;
+  if (c->precision == PFC_PRECISION_BF16) {
+    switch (nc) {
+      case 1: PFC_RUN(__bf16, 1);
+      case 2: PFC_RUN(__bf16, 2);
+      case 3: PFC_RUN(__bf16, 3);
+      case 4: PFC_RUN(__bf16, 4);
+    }
+  } else {
+    switch (nc) {
+      case 1: PFC_RUN(float, 1);
+      case 2: PFC_RUN(float, 2);
+      case 3: PFC_RUN(float, 3);
+      case 4: PFC_RUN(float, 4);
+    }
+  }
+#undef PFC_RUN
+  return PFC_EINVAL;
 }
 
 }  // namespace pfc

@@ -11,6 +11,7 @@ namespace pfc {
 
 namespace {
 
+template <int NC>
 __global__ void update_kernel(float* __restrict__ W, float* __restrict__ V, int64_t N,
                               const int32_t* __restrict__ idx, int64_t k,
                               const float* __restrict__ dWn, int D, float lr, float mu,
@@ -23,9 +24,10 @@ __global__ void update_kernel(float* __restrict__ W, float* __restrict__ V, int6
     if (lane == 0) atomicOr(err_flag, 8);
     return;
   }
-  const int nchunk = D >> 8;
-  float4 w[4], g[4], v[4];
+  constexpr int nchunk = NC;   // D = 256 * NC
+  float4 w[NC], g[NC], v[NC];
   float ww = 0.f, gw = 0.f;
+#pragma unroll
   for (int c = 0; c < nchunk; ++c) {
     const int d = c * 256 + lane * 4;
     w[c] = *reinterpret_cast<const float4*>(W + row * D + d);
@@ -38,6 +40,7 @@ __global__ void update_kernel(float* __restrict__ W, float* __restrict__ V, int6
   gw = wave_sum(gw);
   const float rn = 1.f / fmaxf(sqrtf(ww), 1e-12f);
   const float t = gw * rn * rn;   // <dWn, wn> / |w|  (multiplies the raw row w)
+#pragma unroll
   for (int c = 0; c < nchunk; ++c) {
     const int d = c * 256 + lane * 4;
     float4 vn, wn;
@@ -60,9 +63,20 @@ int update_impl(pfc_ctx* c, float* W, float* v, const int32_t* idx, int64_t k, c
                 float lr, float mu) {
   const int rows_per_block = 4;
   const unsigned grid = (unsigned)((k + rows_per_block - 1) / rows_per_block);
-  PFC_LAUNCH(c, KID_UPDATE, update_kernel, dim3(grid), dim3(rows_per_block * 64), 0, W, v, c->N,
-             idx, k, dW, c->D, lr, mu, c->err_flag);
-  return PFC_OK;
+  switch (c->D / 256) {
+#define PFC_UPD(NC)                                                                              \
+  case NC: {                                                                                     \
+    PFC_LAUNCH(c, KID_UPDATE, update_kernel<NC>, dim3(grid), dim3(rows_per_block * 64), 0, W, v, \
+               c->N, idx, k, dW, c->D, lr, mu, c->err_flag);                                     \
+    return PFC_OK;                                                                               \
+  }
+    PFC_UPD(1)
+    PFC_UPD(2)
+    PFC_UPD(3)
+    PFC_UPD(4)
+#undef PFC_UPD
+  }
+  return PFC_EINVAL;
 }
 
 }  // namespace pfc
