@@ -19,7 +19,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "sample_init",   "sample_mark",  "sample_hist0", "sample_scan0", "sample_hist1",
     "sample_scan1",  "sample_hist2", "sample_scan2", "sample_count", "sample_blkscan",
     "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_logits",
-    "row_combine",   "loss_reduce",  "make_xst",     "gemm_dweight", "dweight_label",
+    "row_combine",   "loss_reduce",  "make_xs",      "gemm_dweight", "dweight_label",
     "gemm_dfeatures", "dfeatures_final", "update"};
 
 static int64_t ceil_rN(int64_t N, double r) { return (int64_t)ceil(r * (double)N); }
@@ -66,7 +66,7 @@ int pfc_destroy(pfc_ctx* c) {
   if (!c) return PFC_EINVAL;
   (void)hipStreamSynchronize(c->stream);
   void* bufs[] = {c->pos_bits, c->hist, c->sel, c->blk_cnt, c->blk_off, c->err_flag, c->Xn,
-                  c->XsT, c->rnormX, c->Wn, c->WnT, c->rnormW, c->E, c->ET, c->rowpart,
+                  c->Xs, c->rnormX, c->Wn, c->rnormW, c->E, c->rowpart,
                   c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
@@ -116,13 +116,11 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(blk_off, (size_t)c->nblk_cap * 2 * 4);
   ALLOC(err_flag, 16);
   ALLOC(Xn, Bp * Dz * es);
-  ALLOC(XsT, Bp * Dz * es);
+  ALLOC(Xs, Bp * Dz * es);
   ALLOC(rnormX, Bp * 4);
   ALLOC(Wn, kp * Dz * es);
-  ALLOC(WnT, kp * Dz * es);
   ALLOC(rnormW, kp * 4);
   ALLOC(E, Bp * kp * es);
-  ALLOC(ET, Bp * kp * es);
   ALLOC(rowpart, (kp / kPadK) * 2 * Bp * 4);
   ALLOC(clabel, Bp * 4);
   ALLOC(rowscale, Bp * 4);

@@ -12,7 +12,7 @@ namespace pfc {
 // Padded problem geometry.  Every scratch operand of the three GEMMs is padded with zeros to a
 // whole number of tiles, so the GEMM main loops need no bounds checks.
 // ---------------------------------------------------------------------------------------------
-constexpr int kPadB = 128;   // batch rows are padded to a multiple of this
+constexpr int kPadB = 256;   // batch rows are padded to a multiple of this
 constexpr int kPadK = 256;   // sampled rows are padded to a multiple of this
 constexpr int kMaxSplits = 64;
 
@@ -37,7 +37,7 @@ enum KernelId {
   KID_GEMM_LOGITS,
   KID_ROW_COMBINE,
   KID_LOSS_REDUCE,
-  KID_MAKE_XST,
+  KID_MAKE_XS,
   KID_GEMM_DW,
   KID_DW_LABEL,
   KID_GEMM_DX,
@@ -84,13 +84,11 @@ struct pfc_ctx {
 
   // forward/backward scratch (T = float or bf16 according to precision)
   void* Xn;        // [Bp x D]   normalised features
-  void* XsT;       // [D x Bp]   (s/(B*l_i)) * xn_i, transposed
+  void* Xs;        // [Bp x D]   (s/(B*l_i)) * xn_i
   float* rnormX;   // [Bp]
   void* Wn;        // [kp x D]   normalised sampled centers
-  void* WnT;       // [D x kp]
   float* rnormW;   // [kp]
   void* E;         // [Bp x kp]  exp(z), label column zeroed
-  void* ET;        // [kp x Bp]
   float* rowpart;  // [tiles_j x Bp] partial row sums of exp(z)
   float* clabel;   // [Bp] cosine of the label column
   float* rowscale; // [Bp] s/(B*l_i)

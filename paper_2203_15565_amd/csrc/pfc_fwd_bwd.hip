@@ -4,11 +4,11 @@
 //
 // Pipeline (one stream, no host synchronisation):
 //   normalize_x        Xn = x/|x|                                   (HBM bound, tiny)
-//   gather_normalize_w Wn = W[idx]/|W[idx]|, plus its transpose     (HBM bound)
-//   gemm_logits        c = Wn Xn^T, margin, e = exp(s c) -> E, ET and per-tile row sums (MFMA)
+//   gather_normalize_w Wn = W[idx]/|W[idx]|                         (HBM bound)
+//   gemm_logits        c = Wn Xn^T, margin, e = exp(s c) -> E and per-tile row sums (MFMA)
 //   row_combine        l_i, lse_i, per-row loss, s/(B l_i), label-column coefficient
 //   loss_reduce        mean loss
-//   make_xst           XsT = ((s/(B l_i)) xn_i)^T
+//   make_xs            Xs = (s/(B l_i)) xn_i
 //   gemm_dweight       dWn = E^T Xs  (off-label part)                (MFMA)
 //   dweight_label      adds the label-column term to the rows of positive classes (fp32)
 //   gemm_dfeatures     partial sums of E Wn over slices of S         (MFMA, split over S)
@@ -77,109 +77,88 @@ __global__ void normalize_x_kernel(const float* __restrict__ X, int B, int Bp, i
 }
 
 // ---------------------------------------------------------------------------------------------
-// gather_normalize_w: a block owns RPB consecutive sampled rows.  Each wavefront normalises
-// RPB/4 rows (coalesced 2 KB row reads of W, ascending row ids), writes them to Wn and into an
-// LDS tile; the block then writes the tile transposed into WnT so that every store instruction
-// covers whole 128-byte segments.  Rows k..kp-1 are written as zeros.
+// gather_normalize_w: one wavefront per group of NB consecutive sampled rows, all NB row reads
+// (2 KB each at D = 512, ascending row ids) in flight before the first is reduced.
+// Rows k..kp-1 of Wn are written as zeros.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int RPB, int NC>
+template <typename T, int NC>
 __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N,
                                           const int32_t* __restrict__ idx, int64_t k, int64_t kp,
-                                          int D, T* __restrict__ Wn, T* __restrict__ WnT,
-                                          float* __restrict__ rnormW,
+                                          int D, T* __restrict__ Wn, float* __restrict__ rnormW,
                                           int32_t* __restrict__ err_flag) {
-  extern __shared__ __align__(16) char smem[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t j0 = (int64_t)blockIdx.x * RPB;
-  const int rowbytes = D * (int)sizeof(T) + 4;   // +4: transposed reads then spread over banks
-  constexpr int nchunk = NC;
-  constexpr int NB = 4;   // rows in flight per wavefront (memory-level parallelism)
-  for (int rb = wave * NB; rb < RPB; rb += 4 * NB) {
-    float4 v[NB][NC];
-    bool ok[NB];
+  constexpr int NB = 4;
+  const int lane = threadIdx.x & 63;
+  const int64_t jb = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * NB;
+  if (jb >= kp) return;
+  float4 v[NB][NC];
+  bool ok[NB];
 #pragma unroll
-    for (int u = 0; u < NB; ++u) {
-      const int64_t j = j0 + rb + u;
-      ok[u] = false;
-      if (j < k) {
-        const int64_t row = idx[j];
-        ok[u] = (row >= 0 && row < N);
-        if (!ok[u] && lane == 0) atomicOr(err_flag, 4);
-        if (ok[u]) {
+  for (int u = 0; u < NB; ++u) {
+    const int64_t j = jb + u;
+    ok[u] = false;
+    if (j < k) {
+      const int64_t row = idx[j];
+      ok[u] = (row >= 0 && row < N);
+      if (!ok[u] && lane == 0) atomicOr(err_flag, 4);
+      if (ok[u]) {
 #pragma unroll
-          for (int c = 0; c < nchunk; ++c)
-            v[u][c] = *reinterpret_cast<const float4*>(W + row * D + c * 256 + lane * 4);
-        }
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < NB; ++u) {
-      const int rr = rb + u;
-      const int64_t j = j0 + rr;
-      float ss = 0.f;
-      if (ok[u])
-#pragma unroll
-        for (int c = 0; c < nchunk; ++c)
-          ss += v[u][c].x * v[u][c].x + v[u][c].y * v[u][c].y + v[u][c].z * v[u][c].z +
-                v[u][c].w * v[u][c].w;
-      ss = wave_sum(ss);
-      const float rn = ok[u] ? 1.f / fmaxf(sqrtf(ss), kEpsNorm) : 0.f;
-      if (lane == 0) rnormW[j] = rn;
-#pragma unroll
-      for (int c = 0; c < nchunk; ++c) {
-        T o[4];
-        if (ok[u]) {
-          o[0] = from_float<T>(v[u][c].x * rn);
-          o[1] = from_float<T>(v[u][c].y * rn);
-          o[2] = from_float<T>(v[u][c].z * rn);
-          o[3] = from_float<T>(v[u][c].w * rn);
-        } else {
-          o[0] = o[1] = o[2] = o[3] = from_float<T>(0.f);
-        }
-        const int d = c * 256 + lane * 4;
-        T* g = Wn + j * D + d;
-        T* sdst = reinterpret_cast<T*>(smem + rr * rowbytes) + d;
-        if constexpr (sizeof(T) == 2) {
-          uint2 pk;
-          __builtin_memcpy(&pk, o, 8);
-          *reinterpret_cast<uint2*>(g) = pk;
-          reinterpret_cast<uint32_t*>(sdst)[0] = pk.x;   // LDS rows are only 4-byte aligned
-          reinterpret_cast<uint32_t*>(sdst)[1] = pk.y;
-        } else {
-          float4 f4;
-          f4.x = (float)o[0]; f4.y = (float)o[1]; f4.z = (float)o[2]; f4.w = (float)o[3];
-          *reinterpret_cast<float4*>(g) = f4;
-          sdst[0] = o[0]; sdst[1] = o[1]; sdst[2] = o[2]; sdst[3] = o[3];
-        }
+        for (int c = 0; c < NC; ++c)
+          v[u][c] = *reinterpret_cast<const float4*>(W + row * D + c * 256 + lane * 4);
       }
     }
   }
-  __syncthreads();
-  // transposed write-out: item (d, q) = 16 bytes = EPV consecutive rows q*EPV.. of column d
-  constexpr int EPV = 16 / (int)sizeof(T);
-  constexpr int QN = RPB / EPV;
-  const int items = D * QN;
-  for (int it = threadIdx.x; it < items; it += blockDim.x) {
-    const int q = it % QN, d = it / QN;
-    T o[EPV];
 #pragma unroll
-    for (int e = 0; e < EPV; ++e)
-      o[e] = reinterpret_cast<const T*>(smem + (q * EPV + e) * rowbytes)[d];
-    uint4 pk;
-    __builtin_memcpy(&pk, o, 16);
-    *reinterpret_cast<uint4*>(WnT + (int64_t)d * kp + j0 + q * EPV) = pk;
+  for (int u = 0; u < NB; ++u) {
+    const int64_t j = jb + u;
+    if (j >= kp) break;
+    float ss = 0.f;
+    if (ok[u]) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+        ss += v[u][c].x * v[u][c].x + v[u][c].y * v[u][c].y + v[u][c].z * v[u][c].z +
+              v[u][c].w * v[u][c].w;
+    }
+    ss = wave_sum(ss);
+    const float rn = ok[u] ? 1.f / fmaxf(sqrtf(ss), kEpsNorm) : 0.f;
+    if (lane == 0) rnormW[j] = rn;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      T o[4];
+      if (ok[u]) {
+        o[0] = from_float<T>(v[u][c].x * rn);
+        o[1] = from_float<T>(v[u][c].y * rn);
+        o[2] = from_float<T>(v[u][c].z * rn);
+        o[3] = from_float<T>(v[u][c].w * rn);
+      } else {
+        o[0] = o[1] = o[2] = o[3] = from_float<T>(0.f);
+      }
+      T* g = Wn + j * D + c * 256 + lane * 4;
+      if constexpr (sizeof(T) == 2) {
+        uint2 pk;
+        __builtin_memcpy(&pk, o, 8);
+        *reinterpret_cast<uint2*>(g) = pk;
+      } else {
+        float4 f4;
+        f4.x = (float)o[0]; f4.y = (float)o[1]; f4.z = (float)o[2]; f4.w = (float)o[3];
+        *reinterpret_cast<float4*>(g) = f4;
+      }
+    }
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// gemm_logits: tile of c[j][i] (rows = sampled classes, columns = samples), fused epilogue.
+// gemm_logits: tile of c[j][i] (rows = sampled classes, columns = samples), fused epilogue:
+// clamp, margin on the label entry, e = exp(s*c), per-tile column sums, and E[i][j] = e (label
+// entry and padding stored as zero).  A lane holds one sample i and runs of 4 consecutive
+// classes j, so the sums over j are in-lane; the bf16 tile is transposed through LDS so that E
+// is written in whole 512-byte rows.
 // ---------------------------------------------------------------------------------------------
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
     const typename Cfg::elem* __restrict__ Wn, const typename Cfg::elem* __restrict__ Xn, int D,
     int64_t k, int B, int Bp, int64_t kp, const int32_t* __restrict__ yl, float s, float cos_m,
-    float sin_m, typename Cfg::elem* __restrict__ E, typename Cfg::elem* __restrict__ ET,
-    float* __restrict__ rowpart, float* __restrict__ clabel, int tiles_j, int tiles_i) {
+    float sin_m, typename Cfg::elem* __restrict__ E, float* __restrict__ rowpart,
+    float* __restrict__ clabel, int tiles_j, int tiles_i) {
   using T = typename Cfg::elem;
   extern __shared__ __align__(16) char smem[];
   int tj, ti;
@@ -188,63 +167,66 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
   const int i0 = ti * Cfg::BN;
 
   f32x16 acc[Cfg::TM][Cfg::TN];
-#pragma unroll
-  for (int a = 0; a < Cfg::TM; ++a)
-#pragma unroll
-    for (int b = 0; b < Cfg::TN; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  zero_acc<Cfg>(acc);
+  gemm_tile<Cfg>(Wn + j0 * D, D, Xn + (int64_t)i0 * D, D, D / Cfg::BK, smem, acc);
 
-  gemm_tile_nt<Cfg>(Wn + j0 * D, D, Xn + (int64_t)i0 * D, D, D / Cfg::BK, smem, acc);
-
+  constexpr bool kStage = (sizeof(T) == 2);          // bf16: transpose the tile through LDS
+  constexpr int SX = Cfg::BM * 2 + 8;                // staging row (one sample) stride in bytes
+  constexpr int RED_OFF = Cfg::BN * SX;              // cross-wave reduction scratch behind it
+  static_assert(RED_OFF + Cfg::WM * Cfg::BN * 4 <= Cfg::LDS_BYTES, "epilogue LDS");
   float colsum[Cfg::TN];
+  const int64_t krem = k - j0;
+  const int klim = krem < (int64_t)Cfg::BM ? (int)krem : Cfg::BM;   // valid classes in this tile
 #pragma unroll
   for (int bn = 0; bn < Cfg::TN; ++bn) {
-    const int i = i0 + acc_col<Cfg>(bn);
+    const int il = acc_col<Cfg>(bn);
+    const int i = i0 + il;
     const bool vi = i < B;
-    const int32_t y = vi ? yl[i] : -1;
-    float sum = 0.f;
+    int yloc = -1;                                   // label position inside this tile, if any
+    if (vi) {
+      const int64_t y = (int64_t)yl[i] - j0;
+      if (y >= 0 && y < (int64_t)klim) yloc = (int)y;
+    }
+    float sum = 0.f, clab = 0.f;
+    bool hit = false;
 #pragma unroll
     for (int bm = 0; bm < Cfg::TM; ++bm) {
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         T pack[4];
-        const int64_t jb = j0 + acc_row<Cfg>(bm, g4 * 4);
+        const int jl = acc_row<Cfg>(bm, g4 * 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int64_t j = jb + e;
           float c = acc[bm][bn][g4 * 4 + e];
           c = fminf(fmaxf(c, -1.f), 1.f);
-          const bool lab = (j == (int64_t)y);
-          float z = s * c;
-          if (lab) z = s * (c * cos_m - sqrtf(fmaxf(1.f - c * c, 0.f)) * sin_m);
+          const bool lab = (jl + e == yloc);
+          const float zl = s * (c * cos_m - sqrtf(fmaxf(1.f - c * c, 0.f)) * sin_m);
+          const float z = lab ? zl : s * c;
           float ev = __expf(z);
-          if (!(vi && j < k)) ev = 0.f;
+          ev = (vi && jl + e < klim) ? ev : 0.f;
           sum += ev;
-          if (lab && vi && j < k) {
-            clabel[i] = c;
-            ev = 0.f;
-          }
-          pack[e] = from_float<T>(ev);
-          ET[j * Bp + i] = pack[e];
+          clab = lab ? c : clab;
+          hit = hit || lab;
+          pack[e] = from_float<T>(lab ? 0.f : ev);
         }
-        T* edst = E + (int64_t)i * kp + jb;
-        if constexpr (sizeof(T) == 2) {
+        if constexpr (kStage) {
           uint2 pk;
           __builtin_memcpy(&pk, pack, 8);
-          *reinterpret_cast<uint2*>(edst) = pk;
+          *reinterpret_cast<uint2*>(smem + il * SX + jl * 2) = pk;
         } else {
           uint4 pk;
           __builtin_memcpy(&pk, pack, 16);
-          *reinterpret_cast<uint4*>(edst) = pk;
+          *reinterpret_cast<uint4*>(E + (int64_t)i * kp + j0 + jl) = pk;
         }
+        __builtin_amdgcn_sched_barrier(0);   // keep the live range to one run of 4 entries
       }
     }
+    if (hit) clabel[i] = clab;   // exactly one lane of one tile holds sample i's label entry
     sum += __shfl_xor(sum, 32, 64);
     colsum[bn] = sum;
   }
   // cross-wave reduction over the WM wavefronts that share a column (fixed order)
-  float* red = reinterpret_cast<float*>(smem);   // [WM][BN]
+  float* red = reinterpret_cast<float*>(smem + RED_OFF);   // [WM][BN]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane < 32) {
 #pragma unroll
@@ -257,6 +239,14 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
 #pragma unroll
     for (int w = 0; w < Cfg::WM; ++w) v += red[w * Cfg::BN + t];
     rowpart[(int64_t)tj * Bp + i0 + t] = v;
+  }
+  if constexpr (kStage) {
+    // one wavefront instruction stores one whole row of the tile: BM * 2 bytes, 8 per lane
+    static_assert(Cfg::BM == 256, "row write-out assumes 64 lanes x 4 classes");
+    for (int row = wave; row < Cfg::BN; row += Cfg::THREADS / 64) {
+      const uint2 v = *reinterpret_cast<const uint2*>(smem + row * SX + lane * 8);
+      *reinterpret_cast<uint2*>(E + (int64_t)(i0 + row) * kp + j0 + lane * 4) = v;
+    }
   }
 }
 
@@ -312,45 +302,49 @@ __global__ void loss_reduce_kernel(const float* __restrict__ lossrow, int B,
   if (threadIdx.x == 0) loss_out[0] = sm[0] / (float)B;
 }
 
-// XsT[d][i] = (s/(B l_i)) * x_i[d]/|x_i| (zero for padded i); 32x32 LDS transpose.
+// Xs[i][d] = (s/(B l_i)) * x_i[d]/|x_i| (zero rows for padded i).
 template <typename T>
-__global__ void make_xst_kernel(const float* __restrict__ X, int B, int Bp, int D,
-                                const float* __restrict__ rnormX,
-                                const float* __restrict__ rowscale, T* __restrict__ XsT) {
-  __shared__ float tile[32][33];
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
-  const int i0 = blockIdx.x * 32, d0 = blockIdx.y * 32;
-  for (int r = ty; r < 32; r += 8) {
-    const int i = i0 + r;
-    float v = 0.f;
-    if (i < B) v = X[(int64_t)i * D + d0 + tx] * rnormX[i] * rowscale[i];
-    tile[r][tx] = v;
+__global__ void make_xs_kernel(const float* __restrict__ X, int B, int Bp, int D,
+                               const float* __restrict__ rnormX,
+                               const float* __restrict__ rowscale, T* __restrict__ Xs) {
+  const int64_t e4 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // group of 4 elements
+  const int64_t total = (int64_t)Bp * D / 4;
+  if (e4 >= total) return;
+  const int i = (int)(e4 * 4 / D);
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < B) {
+    v = *reinterpret_cast<const float4*>(X + e4 * 4);
+    const float f = rnormX[i] * rowscale[i];
+    v.x *= f; v.y *= f; v.z *= f; v.w *= f;
   }
-  __syncthreads();
-  for (int r = ty; r < 32; r += 8)
-    XsT[(int64_t)(d0 + r) * Bp + i0 + tx] = from_float<T>(tile[tx][r]);
+  T o[4] = {from_float<T>(v.x), from_float<T>(v.y), from_float<T>(v.z), from_float<T>(v.w)};
+  if constexpr (sizeof(T) == 2) {
+    uint2 pk;
+    __builtin_memcpy(&pk, o, 8);
+    *reinterpret_cast<uint2*>(Xs + e4 * 4) = pk;
+  } else {
+    uint4 pk;
+    __builtin_memcpy(&pk, o, 16);
+    *reinterpret_cast<uint4*>(Xs + e4 * 4) = pk;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
-// gemm_dweight: dWn[j][d] = sum_i ET[j][i] * XsT[d][i]; rows j < k are written.
+// gemm_dweight: dWn[j][d] = sum_i E[i][j] * Xs[i][d] (both operands k-major); rows j < k are
+// written.
 // ---------------------------------------------------------------------------------------------
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_kernel(
-    const typename Cfg::elem* __restrict__ ET, const typename Cfg::elem* __restrict__ XsT, int D,
-    int64_t k, int Bp, float* __restrict__ dW, int tiles_j, int tiles_d) {
+    const typename Cfg::elem* __restrict__ E, const typename Cfg::elem* __restrict__ Xs, int D,
+    int64_t k, int64_t kp, int Bp, float* __restrict__ dW, int tiles_j, int tiles_d) {
   extern __shared__ __align__(16) char smem[];
   int tj, td;
   if (!xcd_tile(blockIdx.x, tiles_d, tiles_j, tj, td)) return;
   const int64_t j0 = (int64_t)tj * Cfg::BM;
   const int d0 = td * Cfg::BN;
   f32x16 acc[Cfg::TM][Cfg::TN];
-#pragma unroll
-  for (int a = 0; a < Cfg::TM; ++a)
-#pragma unroll
-    for (int b = 0; b < Cfg::TN; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-  gemm_tile_nt<Cfg>(ET + j0 * Bp, Bp, XsT + (int64_t)d0 * Bp, Bp, Bp / Cfg::BK, smem, acc);
+  zero_acc<Cfg>(acc);
+  gemm_tile<Cfg>(E + j0, kp, Xs + d0, D, Bp / Cfg::BK, smem, acc);
 #pragma unroll
   for (int bm = 0; bm < Cfg::TM; ++bm)
 #pragma unroll
@@ -443,11 +437,12 @@ __global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// gemm_dfeatures: slice `sp` of S: part[sp][i][d] = sum_{j in slice} E[i][j] * WnT[d][j].
+// gemm_dfeatures: slice `sp` of S: part[sp][i][d] = sum_{j in slice} E[i][j] * Wn[j][d]
+// (A = E with k contiguous, B = Wn k-major).
 // ---------------------------------------------------------------------------------------------
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_dfeatures_kernel(
-    const typename Cfg::elem* __restrict__ E, const typename Cfg::elem* __restrict__ WnT, int D,
+    const typename Cfg::elem* __restrict__ E, const typename Cfg::elem* __restrict__ Wn, int D,
     int Bp, int64_t kp, int slabs_total, int slabs_per, int splits, float* __restrict__ part,
     int tiles_i, int tiles_d) {
   extern __shared__ __align__(16) char smem[];
@@ -459,15 +454,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_dfeatures_kernel(
   int ns = slabs_total - slab0;
   if (ns > slabs_per) ns = slabs_per;
   f32x16 acc[Cfg::TM][Cfg::TN];
-#pragma unroll
-  for (int a = 0; a < Cfg::TM; ++a)
-#pragma unroll
-    for (int b = 0; b < Cfg::TN; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  zero_acc<Cfg>(acc);
   const int64_t koff = (int64_t)slab0 * Cfg::BK;
-  gemm_tile_nt<Cfg>(E + (int64_t)i0 * kp + koff, kp, WnT + (int64_t)d0 * kp + koff, kp, ns, smem,
-                    acc);
+  gemm_tile<Cfg>(E + (int64_t)i0 * kp + koff, kp, Wn + koff * D + d0, D, ns, smem, acc);
   float* out = part + (int64_t)sp * Bp * D;
 #pragma unroll
   for (int bm = 0; bm < Cfg::TM; ++bm)
@@ -547,71 +536,71 @@ template <typename T, int NC>
 int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t k,
         const int32_t* yl, int32_t B, float s, float m, float* loss_out, float* dX_out,
         float* dW_out) {
-  using CfgF = TileCfg<T, 256, 128, 2, 2>;   // logits: 256 classes x 128 samples
-  using CfgW = TileCfg<T, 256, 128, 2, 2>;   // dweight: 256 classes x 128 of D
-  using CfgX = TileCfg<T, 128, 128, 2, 2>;   // dfeatures: 128 samples x 128 of D
+  using CfgF = TileCfg<T, 256, 256, 2, 4, false, false>;   // logits: 256 classes x 256 samples
+  using CfgW = TileCfg<T, 256, 256, 2, 4, true, true>;     // dweight: 256 classes x 256 of D
+  using CfgX = TileCfg<T, 256, 256, 2, 4, false, true>;    // dfeatures: 256 samples x 256 of D
   const int D = c->D;
   const int Bp = (int)round_up(B, kPadB);
   const int64_t kp = round_up(k, kPadK);
   const float cos_m = cosf(m), sin_m = sinf(m);
-  T* Xn = (T*)c->Xn; T* XsT = (T*)c->XsT; T* Wn = (T*)c->Wn; T* WnT = (T*)c->WnT;
-  T* E = (T*)c->E; T* ET = (T*)c->ET;
+  T* Xn = (T*)c->Xn; T* Xs = (T*)c->Xs; T* Wn = (T*)c->Wn; T* E = (T*)c->E;
 
   auto norm_kernel = normalize_x_kernel<T, NC>;
   PFC_LAUNCH(c, KID_NORM_X, norm_kernel, dim3((Bp + 3) / 4), dim3(256), 0, X, B, Bp, D,
              yl, k, Xn, c->rnormX, c->clabel, c->err_flag);
 
-  constexpr int RPB = sizeof(T) == 2 ? 64 : 32;
-  const size_t gsm = (size_t)RPB * ((size_t)D * sizeof(T) + 4);
-  auto gather_kernel = gather_normalize_w_kernel<T, RPB, NC>;
-  PFC_HIP(hipFuncSetAttribute((const void*)gather_kernel,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)gsm));
-  PFC_LAUNCH(c, KID_GATHER_W, gather_kernel, dim3((unsigned)(kp / RPB)),
-             dim3(256), gsm, W, c->N, idx, k, kp, D, Wn, WnT, c->rnormW, c->err_flag);
+  auto gather_kernel = gather_normalize_w_kernel<T, NC>;
+  PFC_LAUNCH(c, KID_GATHER_W, gather_kernel, dim3((unsigned)((kp / 4 + 3) / 4)), dim3(256), 0, W,
+             c->N, idx, k, kp, D, Wn, c->rnormW, c->err_flag);
 
-  {
-    const int tiles_j = (int)(kp / CfgF::BM), tiles_i = Bp / CfgF::BN;
+  static bool attr_done = false;   // per instantiation: raise the dynamic LDS limit once
+  if (!attr_done) {
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgF>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dfeatures_kernel<CfgX>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgX::LDS_BYTES));
+    attr_done = true;
+  }
+  {
+    const int tiles_j = (int)(kp / CfgF::BM), tiles_i = Bp / CfgF::BN;
     PFC_LAUNCH(c, KID_GEMM_LOGITS, gemm_logits_kernel<CfgF>, dim3(xcd_grid(tiles_i, tiles_j)),
                dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, Bp, kp, yl, s, cos_m, sin_m,
-               E, ET, c->rowpart, c->clabel, tiles_j, tiles_i);
+               E, c->rowpart, c->clabel, tiles_j, tiles_i);
     PFC_LAUNCH(c, KID_ROW_COMBINE, row_combine_kernel, dim3((Bp + 31) / 32), dim3(1024), 0,
                c->rowpart, tiles_j, B, Bp, c->clabel, s, cos_m, sin_m, c->rowscale, c->dlabel,
                c->lossrow);
   }
   PFC_LAUNCH(c, KID_LOSS_REDUCE, loss_reduce_kernel, dim3(1), dim3(256), 0, c->lossrow, B,
              loss_out);
-  PFC_LAUNCH(c, KID_MAKE_XST, make_xst_kernel<T>, dim3(Bp / 32, D / 32), dim3(256), 0, X, B, Bp, D,
-             c->rnormX, c->rowscale, XsT);
+  PFC_LAUNCH(c, KID_MAKE_XS, make_xs_kernel<T>, dim3((unsigned)(((int64_t)Bp * D / 4 + 255) / 256)),
+             dim3(256), 0, X, B, Bp, D, c->rnormX, c->rowscale, Xs);
   {
     const int tiles_j = (int)(kp / CfgW::BM), tiles_d = D / CfgW::BN;
-    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
     PFC_LAUNCH(c, KID_GEMM_DW, gemm_dweight_kernel<CfgW>, dim3(xcd_grid(tiles_d, tiles_j)),
-               dim3(CfgW::THREADS), CfgW::LDS_BYTES, ET, XsT, D, k, Bp, dW_out, tiles_j, tiles_d);
+               dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs, D, k, kp, Bp, dW_out, tiles_j,
+               tiles_d);
   }
-  PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel, dim3(B), dim3(kLabelThreads), 0, X, B, D, yl, k,
-             c->rnormX, c->dlabel, dW_out);
+  PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel, dim3(B), dim3(kLabelThreads), 0, X, B, D, yl,
+             k, c->rnormX, c->dlabel, dW_out);
   int splits;
   {
     const int tiles_i = Bp / CfgX::BM, tiles_d = D / CfgX::BN;
     const int slabs_total = (int)(kp / CfgX::BK);
-    int want = 1024 / (tiles_i * tiles_d);
+    int want = 256 / (tiles_i * tiles_d);
     if (want < 1) want = 1;
     if (want > kMaxSplits) want = kMaxSplits;
     if (want > slabs_total) want = slabs_total;
     const int slabs_per = (slabs_total + want - 1) / want;
     splits = (slabs_total + slabs_per - 1) / slabs_per;
-    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dfeatures_kernel<CfgX>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgX::LDS_BYTES));
     PFC_LAUNCH(c, KID_GEMM_DX, gemm_dfeatures_kernel<CfgX>,
                dim3(xcd_grid(tiles_i * tiles_d, splits)), dim3(CfgX::THREADS), CfgX::LDS_BYTES, E,
-               WnT, D, Bp, kp, slabs_total, slabs_per, splits, c->dXpart, tiles_i, tiles_d);
+               Wn, D, Bp, kp, slabs_total, slabs_per, splits, c->dXpart, tiles_i, tiles_d);
   }
-  PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3((B + 3) / 4), dim3(256), 0, c->dXpart,
-             splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW, c->rowscale,
-             c->dlabel, dX_out);
+  PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3((B + 3) / 4), dim3(256), 0,
+             c->dXpart, splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW,
+             c->rowscale, c->dlabel, dX_out);
   return PFC_OK;
 }
 

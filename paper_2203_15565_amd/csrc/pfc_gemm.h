@@ -1,22 +1,29 @@
 // MFMA tile engine for the three GEMMs of the PFC step (gfx950).
 //
-// All three products are brought to the "NT" form  C[m][n] = sum_k A[m][k] * B[n][k]  with both
-// operands row-major and k contiguous, so that every lane's MFMA fragment is one 16-byte load:
-//   logits    C[j][i] = <Wn_j, Xn_i>                 A = Wn  [kp x D],  B = Xn  [Bp x D]
-//   dweight   C[j][d] = sum_i ET[j][i] * XsT[d][i]   A = ET  [kp x Bp], B = XsT [D x Bp]
-//   dfeatures C[i][d] = sum_j E[i][j]  * WnT[d][j]   A = E   [Bp x kp], B = WnT [D x kp]
-// Operands are padded with zeros to whole tiles by their producers: no bounds checks here.
+//   logits    C[j][i] = sum_d Wn[j][d] * Xn[i][d]        A = Wn  (k contiguous), B = Xn (k contiguous)
+//   dweight   C[j][d] = sum_i E[i][j]  * Xs[i][d]        A = E   (k-major),      B = Xs (k-major)
+//   dfeatures C[i][d] = sum_j E[i][j]  * Wn[j][d]        A = E   (k contiguous), B = Wn (k-major)
+//
+// Every matrix stays in its one natural row-major layout in HBM; an operand whose reduction
+// index is its ROW index ("k-major") is staged in LDS as it is and transposed on the way into
+// the MFMA registers by the LDS transpose read of gfx950 (ds_read_b64_tr_b16), so no transposed
+// copy of E, Wn or Xs is ever written.  Operands are padded with zeros to whole tiles by their
+// producers: the main loop has no bounds checks.
 //
 // A workgroup of WM x WN wavefronts (64 lanes each) owns a BM x BN tile of C.  K is walked in
-// slabs of 128 bytes per row (64 bf16 / 32 fp32); a slab of A and B is staged in LDS (double
-// buffered, rows padded by 16 bytes so that a 16-byte fragment read by 16 consecutive rows
-// touches every bank once) and consumed with v_mfma_f32_32x32x16_bf16 (bf16) or
-// v_mfma_f32_32x32x2_f32 (fp32).
+// slabs of BK = 64 (bf16) or 32 (fp32) reduction steps, double buffered in LDS; global loads of
+// slab s+1 are in flight in registers while slab s is multiplied.
 //
-// Fragment convention (both operands alike, which is all that a dot product needs): within a
-// 32-byte group g of a row, lanes 0..31 take bytes [0,16) and lanes 32..63 bytes [16,32).
-// For bf16 that is 8 consecutive k per lane = one 32x32x16 MFMA; for fp32 it is 4 consecutive k
-// per lane = four 32x32x2 MFMAs, the t-th of which pairs element t of every lane.
+// LDS layouts of one operand slab (R = BM or BN rows of the operand tile):
+//   k contiguous: R rows of 128 bytes, row stride 144: a 16-byte fragment read by 16 consecutive
+//                 rows touches every bank once.
+//   k-major:      BK rows of R*sizeof(T) bytes, row stride + 64: the four k-rows that one
+//                 transpose read gathers fall into different banks.
+//
+// Fragment convention (the same for A and B, which is all a dot product needs): a group of 16
+// (bf16) or 8 (fp32) reduction steps is split between the lane halves, lanes 0..31 taking the
+// first half and lanes 32..63 the second; for bf16 that is one v_mfma_f32_32x32x16_bf16 per
+// group, for fp32 four v_mfma_f32_32x32x2_f32, the t-th of which pairs element t of every lane.
 //
 // Accumulator layout of a 32x32 block (16 floats per lane): register r of lane l holds
 //   row = (r / 4) * 8 + (l / 32) * 4 + (r % 4),  col = l % 32.
@@ -30,25 +37,43 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kSlabBytes = 128;            // bytes of K per row per slab
-constexpr int kLdsRow = kSlabBytes + 16;   // padded LDS row stride
+constexpr int kSlabBytes = 128;   // bytes of K per operand row per slab (k-contiguous layout)
 
-template <typename T, int BM_, int BN_, int WM_, int WN_>
+// Geometry of one operand slab in LDS.
+template <typename T, int R, bool KMAJOR>
+struct OperandLds {
+  static constexpr int BK = kSlabBytes / (int)sizeof(T);
+  static constexpr int ROWS = KMAJOR ? BK : R;                                   // LDS rows
+  static constexpr int ROW_BYTES = KMAJOR ? R * (int)sizeof(T) : kSlabBytes;     // payload
+  static constexpr int STRIDE = ROW_BYTES + (KMAJOR ? 64 : 16);                  // padded
+  static constexpr int BYTES = ROWS * STRIDE;
+  static constexpr int CHUNKS_PER_ROW = ROW_BYTES / 16;
+  static constexpr int CHUNKS = ROWS * CHUNKS_PER_ROW;                           // 16-byte chunks
+};
+
+template <typename T, int BM_, int BN_, int WM_, int WN_, bool AKM, bool BKM>
 struct TileCfg {
   using elem = T;
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
-  static constexpr int BK = kSlabBytes / (int)sizeof(T);   // elements of K per slab
+  static constexpr bool A_KMAJOR = AKM, B_KMAJOR = BKM;
+  static constexpr int BK = kSlabBytes / (int)sizeof(T);   // reduction steps per slab
   static constexpr int THREADS = WM * WN * 64;
   static constexpr int WTM = BM / WM, WTN = BN / WN;       // tile of one wavefront
   static constexpr int TM = WTM / 32, TN = WTN / 32;       // 32x32 blocks per wavefront
-  static constexpr int A_BYTES = BM * kLdsRow, B_BYTES = BN * kLdsRow;
+  using LA = OperandLds<T, BM, AKM>;
+  using LB = OperandLds<T, BN, BKM>;
+  static constexpr int A_BYTES = LA::BYTES, B_BYTES = LB::BYTES;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-  static constexpr int A_CHUNKS = BM * 8 / THREADS;        // 16-byte chunks per thread per slab
-  static constexpr int B_CHUNKS = BN * 8 / THREADS;
+  static constexpr int A_CHUNKS = LA::CHUNKS / THREADS;    // 16-byte chunks per thread per slab
+  static constexpr int B_CHUNKS = LB::CHUNKS / THREADS;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be whole 32x32 blocks");
-  static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "slab must divide evenly");
+  static_assert(LA::CHUNKS % THREADS == 0 && LB::CHUNKS % THREADS == 0, "slab must divide evenly");
+  static_assert(THREADS % LA::CHUNKS_PER_ROW == 0 && THREADS % LB::CHUNKS_PER_ROW == 0,
+                "a staging pass must cover whole LDS rows");
 };
 
 template <typename T>
@@ -71,88 +96,139 @@ __device__ __forceinline__ void mfma_group<float>(const u32x4& a, const u32x4& b
   c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[3], bf[3], c, 0, 0, 0);
 }
 
+// Global -> register -> LDS staging of one operand slab.  Thread t owns chunk (t % CPR) of LDS
+// rows (t / CPR) + p * (THREADS / CPR), p = 0 .. NCH-1.
+template <typename T, class L, int THREADS, int NCH, bool KMAJOR>
+struct Stager {
+  const char* g;      // this thread's first global chunk (slab 0)
+  int64_t pass;       // global byte step between passes
+  int64_t slab;       // global byte step between slabs
+  int lds;            // this thread's first LDS byte offset inside the operand region
+  static constexpr int RPP = THREADS / L::CHUNKS_PER_ROW;   // LDS rows per pass
+
+  // base: element (row 0 of the operand tile, first k of the range); ld in elements.
+  __device__ __forceinline__ void init(const T* base, int64_t ld) {
+    const int t = threadIdx.x;
+    const int row = t / L::CHUNKS_PER_ROW, ch = t % L::CHUNKS_PER_ROW;
+    // k contiguous: LDS row = tile row, advancing a slab moves 128 bytes along the row.
+    // k-major:      LDS row = reduction step, advancing a slab moves BK rows down.
+    g = reinterpret_cast<const char*>(base) + (int64_t)row * ld * (int64_t)sizeof(T) + ch * 16;
+    pass = (int64_t)RPP * ld * (int64_t)sizeof(T);
+    slab = KMAJOR ? (int64_t)L::BK * ld * (int64_t)sizeof(T) : (int64_t)kSlabBytes;
+    lds = row * L::STRIDE + ch * 16;
+  }
+  __device__ __forceinline__ void load(int s, u32x4 (&r)[NCH]) const {
+#pragma unroll
+    for (int p = 0; p < NCH; ++p)
+      r[p] = *reinterpret_cast<const u32x4*>(g + (int64_t)s * slab + p * pass);
+  }
+  __device__ __forceinline__ void store(char* region, const u32x4 (&r)[NCH]) const {
+#pragma unroll
+    for (int p = 0; p < NCH; ++p)
+      *reinterpret_cast<u32x4*>(region + lds + p * RPP * L::STRIDE) = r[p];
+  }
+};
+
+// One 16-byte MFMA fragment of 32 tile rows starting at row `r0`, reduction group `g`
+// (16 steps for bf16, 8 for fp32), from an operand slab in LDS.
+template <typename T, class L, bool KMAJOR>
+__device__ __forceinline__ u32x4 read_frag(const char* region, int r0, int g) {
+  const int lane = threadIdx.x & 63;
+  if constexpr (!KMAJOR) {
+    return *reinterpret_cast<const u32x4*>(region + (r0 + (lane & 31)) * L::STRIDE + g * 32 +
+                                           (lane >> 5) * 16);
+  } else if constexpr (sizeof(T) == 2) {
+    // ds_read_b64_tr_b16: inside each group of 16 lanes, lane s addresses the 4 consecutive tile
+    // rows r0' + 4*(s%4).. of reduction step k0 + s/4, and lane i receives tile row r0' + i for
+    // the 4 steps k0..k0+3.  Lane groups: (rows 0..15 | 16..31) x (first | second half of the group).
+    const int grp = lane >> 4, s = lane & 15;
+    const int k0 = g * 16 + (grp >> 1) * 8 + (s >> 2);
+    const int col = r0 + (grp & 1) * 16 + (s & 3) * 4;
+    const char* p = region + k0 * L::STRIDE + col * 2;
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * L::STRIDE));
+    const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    u32x4 r;
+    r[0] = l2[0]; r[1] = l2[1]; r[2] = h2[0]; r[3] = h2[1];
+    return r;
+  } else {
+    // fp32: four scalar reads, reduction steps g*8 + half*4 + 0..3 of tile row r0 + lane%32
+    const char* p = region + (g * 8 + (lane >> 5) * 4) * L::STRIDE + (r0 + (lane & 31)) * 4;
+    u32x4 r;
+    r[0] = *reinterpret_cast<const uint32_t*>(p);
+    r[1] = *reinterpret_cast<const uint32_t*>(p + L::STRIDE);
+    r[2] = *reinterpret_cast<const uint32_t*>(p + 2 * L::STRIDE);
+    r[3] = *reinterpret_cast<const uint32_t*>(p + 3 * L::STRIDE);
+    return r;
+  }
+}
+
 // Accumulate acc += A_tile * B_tile^T over `nslabs` slabs of K.
-//   A: first row of this workgroup's BM rows, at the first k of its range; lda in elements.
-//   B: likewise for its BN rows.
-//   smem: Cfg::LDS_BYTES bytes, 16-byte aligned.
+//   A: element (first of this workgroup's BM tile rows, first reduction step of its range)
+//   B: likewise for its BN tile rows;  lda / ldb in elements.
+//   smem: Cfg::LDS_BYTES bytes, 16-byte aligned.  Ends with a barrier (smem may be reused).
 template <class Cfg>
-__device__ __forceinline__ void gemm_tile_nt(const typename Cfg::elem* __restrict__ A, int64_t lda,
-                                             const typename Cfg::elem* __restrict__ B, int64_t ldb,
-                                             int nslabs, char* smem,
-                                             f32x16 (&acc)[Cfg::TM][Cfg::TN]) {
+__device__ __forceinline__ void gemm_tile(const typename Cfg::elem* __restrict__ A, int64_t lda,
+                                          const typename Cfg::elem* __restrict__ B, int64_t ldb,
+                                          int nslabs, char* smem,
+                                          f32x16 (&acc)[Cfg::TM][Cfg::TN]) {
   using T = typename Cfg::elem;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  using LA = typename Cfg::LA;
+  using LB = typename Cfg::LB;
+  const int wave = threadIdx.x >> 6;
   const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
-  const int half = lane >> 5, l32 = lane & 31;
 
-  // global -> LDS staging: thread handles chunk (tid % 8) of rows (tid / 8) + i * THREADS/8
-  const int ld_row = tid >> 3, ld_chunk = tid & 7;
-  constexpr int ROWS_PER_PASS = Cfg::THREADS / 8;
-  const char* gA = reinterpret_cast<const char*>(A) + (int64_t)ld_row * lda * (int64_t)sizeof(T) +
-                   ld_chunk * 16;
-  const char* gB = reinterpret_cast<const char*>(B) + (int64_t)ld_row * ldb * (int64_t)sizeof(T) +
-                   ld_chunk * 16;
-  const int64_t strideA = (int64_t)ROWS_PER_PASS * lda * (int64_t)sizeof(T);
-  const int64_t strideB = (int64_t)ROWS_PER_PASS * ldb * (int64_t)sizeof(T);
-  const int st_off = ld_row * kLdsRow + ld_chunk * 16;
-
+  Stager<T, LA, Cfg::THREADS, Cfg::A_CHUNKS, Cfg::A_KMAJOR> sa;
+  Stager<T, LB, Cfg::THREADS, Cfg::B_CHUNKS, Cfg::B_KMAJOR> sb;
+  sa.init(A, lda);
+  sb.init(B, ldb);
   u32x4 ra[Cfg::A_CHUNKS], rb[Cfg::B_CHUNKS];
-
-#pragma unroll
-  for (int i = 0; i < Cfg::A_CHUNKS; ++i)
-    ra[i] = *reinterpret_cast<const u32x4*>(gA + i * strideA);
-#pragma unroll
-  for (int i = 0; i < Cfg::B_CHUNKS; ++i)
-    rb[i] = *reinterpret_cast<const u32x4*>(gB + i * strideB);
-#pragma unroll
-  for (int i = 0; i < Cfg::A_CHUNKS; ++i)
-    *reinterpret_cast<u32x4*>(smem + st_off + i * ROWS_PER_PASS * kLdsRow) = ra[i];
-#pragma unroll
-  for (int i = 0; i < Cfg::B_CHUNKS; ++i)
-    *reinterpret_cast<u32x4*>(smem + Cfg::A_BYTES + st_off + i * ROWS_PER_PASS * kLdsRow) = rb[i];
+  sa.load(0, ra);
+  sb.load(0, rb);
+  sa.store(smem, ra);
+  sb.store(smem + Cfg::A_BYTES, rb);
   __syncthreads();
 
-  const int fa_off = (wm * Cfg::WTM + l32) * kLdsRow + half * 16;
-  const int fb_off = Cfg::A_BYTES + (wn * Cfg::WTN + l32) * kLdsRow + half * 16;
-
+  constexpr int GROUPS = kSlabBytes / 32;   // fragment groups per slab
   for (int s = 0; s < nslabs; ++s) {
     const char* cur = smem + (s & 1) * Cfg::STAGE_BYTES;
     char* nxt = smem + ((s + 1) & 1) * Cfg::STAGE_BYTES;
     const bool more = (s + 1 < nslabs);
     if (more) {
-      const int64_t koff = (int64_t)(s + 1) * kSlabBytes;
-#pragma unroll
-      for (int i = 0; i < Cfg::A_CHUNKS; ++i)
-        ra[i] = *reinterpret_cast<const u32x4*>(gA + koff + i * strideA);
-#pragma unroll
-      for (int i = 0; i < Cfg::B_CHUNKS; ++i)
-        rb[i] = *reinterpret_cast<const u32x4*>(gB + koff + i * strideB);
+      sa.load(s + 1, ra);
+      sb.load(s + 1, rb);
     }
 #pragma unroll
-    for (int g = 0; g < kSlabBytes / 32; ++g) {
+    for (int g = 0; g < GROUPS; ++g) {
       u32x4 fa[Cfg::TM], fb[Cfg::TN];
 #pragma unroll
       for (int bm = 0; bm < Cfg::TM; ++bm)
-        fa[bm] = *reinterpret_cast<const u32x4*>(cur + fa_off + bm * 32 * kLdsRow + g * 32);
+        fa[bm] = read_frag<T, LA, Cfg::A_KMAJOR>(cur, wm * Cfg::WTM + bm * 32, g);
 #pragma unroll
       for (int bn = 0; bn < Cfg::TN; ++bn)
-        fb[bn] = *reinterpret_cast<const u32x4*>(cur + fb_off + bn * 32 * kLdsRow + g * 32);
+        fb[bn] = read_frag<T, LB, Cfg::B_KMAJOR>(cur + Cfg::A_BYTES, wn * Cfg::WTN + bn * 32, g);
 #pragma unroll
       for (int bm = 0; bm < Cfg::TM; ++bm)
 #pragma unroll
         for (int bn = 0; bn < Cfg::TN; ++bn) mfma_group<T>(fa[bm], fb[bn], acc[bm][bn]);
     }
     if (more) {
-#pragma unroll
-      for (int i = 0; i < Cfg::A_CHUNKS; ++i)
-        *reinterpret_cast<u32x4*>(nxt + st_off + i * ROWS_PER_PASS * kLdsRow) = ra[i];
-#pragma unroll
-      for (int i = 0; i < Cfg::B_CHUNKS; ++i)
-        *reinterpret_cast<u32x4*>(nxt + Cfg::A_BYTES + st_off + i * ROWS_PER_PASS * kLdsRow) = rb[i];
+      sa.store(nxt, ra);
+      sb.store(nxt + Cfg::A_BYTES, rb);
     }
     __syncthreads();
   }
+}
+
+template <class Cfg>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[Cfg::TM][Cfg::TN]) {
+#pragma unroll
+  for (int a = 0; a < Cfg::TM; ++a)
+#pragma unroll
+    for (int b = 0; b < Cfg::TN; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 }
 
 // Row / column of accumulator register r of block (bm, bn) inside the workgroup tile.
