@@ -152,7 +152,67 @@ __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N
 // entry and padding stored as zero).  A lane holds one sample i and runs of 4 consecutive
 // classes j, so the sums over j are in-lane; the bf16 tile is transposed through LDS so that E
 // is written in whole 512-byte rows.
+//
+// The element-wise part exists twice.  The plain version (5 VALU instructions per entry) serves
+// wavefronts whose part of the tile holds no label entry and no padding; only the few
+// wavefronts that do hold one take the guarded version.
 // ---------------------------------------------------------------------------------------------
+template <class Cfg, bool GUARDED>
+__device__ __forceinline__ void logits_epilogue_columns(
+    const f32x16 (&acc)[Cfg::TM][Cfg::TN], int64_t j0, int i0, int B, int klim, int64_t kp,
+    const int (&ylane)[Cfg::TN], float s, float s_log2e, float cos_m, float sin_m, char* smem,
+    int SX, typename Cfg::elem* __restrict__ E, float* __restrict__ clabel,
+    float (&colsum)[Cfg::TN]) {
+  using T = typename Cfg::elem;
+  constexpr bool kStage = (sizeof(T) == 2);
+#pragma unroll
+  for (int bn = 0; bn < Cfg::TN; ++bn) {
+    const int il = acc_col<Cfg>(bn);
+    const int i = i0 + il;
+    const bool vi = i < B;
+    const int yloc = ylane[bn];
+    float sum = 0.f, clab = 0.f;
+#pragma unroll
+    for (int bm = 0; bm < Cfg::TM; ++bm) {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        T pack[4];
+        const int jl = acc_row<Cfg>(bm, g4 * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float c = __builtin_amdgcn_fmed3f(acc[bm][bn][g4 * 4 + e], -1.f, 1.f);
+          float ev = __builtin_amdgcn_exp2f(c * s_log2e);   // exp(s*c); |s*c*log2(e)| <= 93
+          if constexpr (GUARDED) {
+            const bool lab = (jl + e == yloc);
+            ev = (vi && jl + e < klim && !lab) ? ev : 0.f;
+            clab = lab ? c : clab;
+          }
+          sum += ev;
+          pack[e] = from_float<T>(ev);
+        }
+        if constexpr (kStage) {
+          uint2 pk;
+          __builtin_memcpy(&pk, pack, 8);
+          *reinterpret_cast<uint2*>(smem + il * SX + jl * 2) = pk;
+        } else {
+          uint4 pk;
+          __builtin_memcpy(&pk, pack, 16);
+          *reinterpret_cast<uint4*>(E + (int64_t)i * kp + j0 + jl) = pk;
+        }
+      }
+    }
+    if constexpr (GUARDED) {
+      if (yloc >= 0) {   // this lane holds sample i's label entry: it was left out of `sum`
+        clabel[i] = clab;
+        const float zl = s * (clab * cos_m - sqrtf(fmaxf(1.f - clab * clab, 0.f)) * sin_m);
+        sum += __expf(zl);
+      }
+    }
+    sum += __shfl_xor(sum, 32, 64);
+    colsum[bn] = sum;
+  }
+}
+
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
     const typename Cfg::elem* __restrict__ Wn, const typename Cfg::elem* __restrict__ Xn, int D,
@@ -174,60 +234,40 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
   constexpr int SX = Cfg::BM * 2 + 8;                // staging row (one sample) stride in bytes
   constexpr int RED_OFF = Cfg::BN * SX;              // cross-wave reduction scratch behind it
   static_assert(RED_OFF + Cfg::WM * Cfg::BN * 4 <= Cfg::LDS_BYTES, "epilogue LDS");
-  float colsum[Cfg::TN];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t krem = k - j0;
   const int klim = krem < (int64_t)Cfg::BM ? (int)krem : Cfg::BM;   // valid classes in this tile
+
+  // ylane[bn]: tile row of sample i's label entry if THIS lane holds it, else -1.  A lane holds
+  // the rows  wm*WTM + bm*32 + (r/4)*8 + half*4 + r%4.
+  int ylane[Cfg::TN];
+  bool any_label = false;
 #pragma unroll
   for (int bn = 0; bn < Cfg::TN; ++bn) {
-    const int il = acc_col<Cfg>(bn);
-    const int i = i0 + il;
-    const bool vi = i < B;
-    int yloc = -1;                                   // label position inside this tile, if any
-    if (vi) {
+    const int i = i0 + acc_col<Cfg>(bn);
+    ylane[bn] = -1;
+    if (i < B) {
       const int64_t y = (int64_t)yl[i] - j0;
-      if (y >= 0 && y < (int64_t)klim) yloc = (int)y;
-    }
-    float sum = 0.f, clab = 0.f;
-    bool hit = false;
-#pragma unroll
-    for (int bm = 0; bm < Cfg::TM; ++bm) {
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        T pack[4];
-        const int jl = acc_row<Cfg>(bm, g4 * 4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float c = acc[bm][bn][g4 * 4 + e];
-          c = fminf(fmaxf(c, -1.f), 1.f);
-          const bool lab = (jl + e == yloc);
-          const float zl = s * (c * cos_m - sqrtf(fmaxf(1.f - c * c, 0.f)) * sin_m);
-          const float z = lab ? zl : s * c;
-          float ev = __expf(z);
-          ev = (vi && jl + e < klim) ? ev : 0.f;
-          sum += ev;
-          clab = lab ? c : clab;
-          hit = hit || lab;
-          pack[e] = from_float<T>(lab ? 0.f : ev);
-        }
-        if constexpr (kStage) {
-          uint2 pk;
-          __builtin_memcpy(&pk, pack, 8);
-          *reinterpret_cast<uint2*>(smem + il * SX + jl * 2) = pk;
-        } else {
-          uint4 pk;
-          __builtin_memcpy(&pk, pack, 16);
-          *reinterpret_cast<uint4*>(E + (int64_t)i * kp + j0 + jl) = pk;
-        }
-        __builtin_amdgcn_sched_barrier(0);   // keep the live range to one run of 4 entries
+      if (y >= 0 && y < (int64_t)klim) {
+        const int rel = (int)y - (wave / Cfg::WN) * Cfg::WTM;
+        if (rel >= 0 && rel < Cfg::WTM && ((rel >> 2) & 1) == (lane >> 5)) ylane[bn] = (int)y;
       }
     }
-    if (hit) clabel[i] = clab;   // exactly one lane of one tile holds sample i's label entry
-    sum += __shfl_xor(sum, 32, 64);
-    colsum[bn] = sum;
+    any_label = any_label || (ylane[bn] >= 0);
   }
+  const bool guarded = __any(any_label) || klim < Cfg::BM || i0 + Cfg::BN > B;   // wave-uniform
+
+  const float s_log2e = s * 1.44269504088896340736f;
+  float colsum[Cfg::TN];
+  if (guarded)
+    logits_epilogue_columns<Cfg, true>(acc, j0, i0, B, klim, kp, ylane, s, s_log2e, cos_m, sin_m,
+                                       smem, SX, E, clabel, colsum);
+  else
+    logits_epilogue_columns<Cfg, false>(acc, j0, i0, B, klim, kp, ylane, s, s_log2e, cos_m, sin_m,
+                                        smem, SX, E, clabel, colsum);
+
   // cross-wave reduction over the WM wavefronts that share a column (fixed order)
   float* red = reinterpret_cast<float*>(smem + RED_OFF);   // [WM][BN]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane < 32) {
 #pragma unroll
     for (int bn = 0; bn < Cfg::TN; ++bn)
@@ -536,9 +576,9 @@ template <typename T, int NC>
 int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t k,
         const int32_t* yl, int32_t B, float s, float m, float* loss_out, float* dX_out,
         float* dW_out) {
-  using CfgF = TileCfg<T, 256, 256, 2, 4, false, false>;   // logits: 256 classes x 256 samples
-  using CfgW = TileCfg<T, 256, 256, 2, 4, true, true>;     // dweight: 256 classes x 256 of D
-  using CfgX = TileCfg<T, 256, 256, 2, 4, false, true>;    // dfeatures: 256 samples x 256 of D
+  using CfgF = TileCfg<T, 256, 256, 2, 4, false, false, 1>;   // logits: 256 classes x 256 samples
+  using CfgW = TileCfg<T, 256, 256, 2, 4, true, true, 1>;   // dweight: 256 classes x 256 of D
+  using CfgX = TileCfg<T, 256, 256, 2, 4, false, true, 2>;   // dfeatures: 256 samples x 256 of D
   const int D = c->D;
   const int Bp = (int)round_up(B, kPadB);
   const int64_t kp = round_up(k, kPadK);

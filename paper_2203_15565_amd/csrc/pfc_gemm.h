@@ -54,11 +54,12 @@ struct OperandLds {
   static constexpr int CHUNKS = ROWS * CHUNKS_PER_ROW;                           // 16-byte chunks
 };
 
-template <typename T, int BM_, int BN_, int WM_, int WN_, bool AKM, bool BKM>
+template <typename T, int BM_, int BN_, int WM_, int WN_, bool AKM, bool BKM, int DIST_ = 2>
 struct TileCfg {
   using elem = T;
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
   static constexpr bool A_KMAJOR = AKM, B_KMAJOR = BKM;
+  static constexpr int DIST = DIST_;   // global-load prefetch distance in slabs (1 or 2)
   static constexpr int BK = kSlabBytes / (int)sizeof(T);   // reduction steps per slab
   static constexpr int THREADS = WM * WN * 64;
   static constexpr int WTM = BM / WM, WTN = BN / WN;       // tile of one wavefront
@@ -97,35 +98,50 @@ __device__ __forceinline__ void mfma_group<float>(const u32x4& a, const u32x4& b
 }
 
 // Global -> register -> LDS staging of one operand slab.  Thread t owns chunk (t % CPR) of LDS
-// rows (t / CPR) + p * (THREADS / CPR), p = 0 .. NCH-1.
+// rows (t / CPR) + p * (THREADS / CPR), p = 0 .. NCH-1.  Addresses are a wave-uniform 64-bit
+// base (tile, slab, pass) plus one 32-bit per-thread offset, which lets the loads use the
+// scalar-base addressing form and keeps address registers out of the vector register budget.
 template <typename T, class L, int THREADS, int NCH, bool KMAJOR>
 struct Stager {
-  const char* g;      // this thread's first global chunk (slab 0)
-  int64_t pass;       // global byte step between passes
-  int64_t slab;       // global byte step between slabs
+  const char* base;   // wave-uniform: first byte of the operand tile at the first k of the range
+  uint32_t toff;      // this thread's byte offset from the pass base
+  int64_t pass;       // global byte step between passes (uniform)
+  int64_t slab;       // global byte step between slabs (uniform)
   int lds;            // this thread's first LDS byte offset inside the operand region
   static constexpr int RPP = THREADS / L::CHUNKS_PER_ROW;   // LDS rows per pass
 
-  // base: element (row 0 of the operand tile, first k of the range); ld in elements.
-  __device__ __forceinline__ void init(const T* base, int64_t ld) {
+  // tile: element (row 0 of the operand tile, first k of the range); ld in elements.
+  __device__ __forceinline__ void init(const T* tile, int64_t ld) {
     const int t = threadIdx.x;
     const int row = t / L::CHUNKS_PER_ROW, ch = t % L::CHUNKS_PER_ROW;
     // k contiguous: LDS row = tile row, advancing a slab moves 128 bytes along the row.
     // k-major:      LDS row = reduction step, advancing a slab moves BK rows down.
-    g = reinterpret_cast<const char*>(base) + (int64_t)row * ld * (int64_t)sizeof(T) + ch * 16;
+    base = reinterpret_cast<const char*>(tile);
+    toff = (uint32_t)((int64_t)row * ld * (int64_t)sizeof(T) + ch * 16);
     pass = (int64_t)RPP * ld * (int64_t)sizeof(T);
     slab = KMAJOR ? (int64_t)L::BK * ld * (int64_t)sizeof(T) : (int64_t)kSlabBytes;
     lds = row * L::STRIDE + ch * 16;
   }
-  __device__ __forceinline__ void load(int s, u32x4 (&r)[NCH]) const {
+  // The chunks of one slab live in ONE vector value (not an array), so they are registers by
+  // construction whatever the control flow around the loads.
+  typedef uint32_t Regs __attribute__((ext_vector_type(NCH * 4)));
+  __device__ __forceinline__ Regs load(int s) const {
+    const char* sb = base + (int64_t)s * slab;
+    Regs r;
 #pragma unroll
-    for (int p = 0; p < NCH; ++p)
-      r[p] = *reinterpret_cast<const u32x4*>(g + (int64_t)s * slab + p * pass);
+    for (int p = 0; p < NCH; ++p) {
+      const u32x4 t = *reinterpret_cast<const u32x4*>(sb + p * pass + toff);
+      r[4 * p + 0] = t[0]; r[4 * p + 1] = t[1]; r[4 * p + 2] = t[2]; r[4 * p + 3] = t[3];
+    }
+    return r;
   }
-  __device__ __forceinline__ void store(char* region, const u32x4 (&r)[NCH]) const {
+  __device__ __forceinline__ void store(char* region, const Regs& r) const {
 #pragma unroll
-    for (int p = 0; p < NCH; ++p)
-      *reinterpret_cast<u32x4*>(region + lds + p * RPP * L::STRIDE) = r[p];
+    for (int p = 0; p < NCH; ++p) {
+      u32x4 t;
+      t[0] = r[4 * p + 0]; t[1] = r[4 * p + 1]; t[2] = r[4 * p + 2]; t[3] = r[4 * p + 3];
+      *reinterpret_cast<u32x4*>(region + lds + p * RPP * L::STRIDE) = t;
+    }
   }
 };
 
@@ -164,10 +180,65 @@ __device__ __forceinline__ u32x4 read_frag(const char* region, int r0, int g) {
   }
 }
 
+// The MFMA fragments of one reduction group for a whole wavefront tile.
+template <class Cfg>
+struct Frags {
+  u32x4 a[Cfg::TM];
+  u32x4 b[Cfg::TN];
+};
+
+template <class Cfg>
+__device__ __forceinline__ void read_group(const char* stage, int g, int wm, int wn,
+                                           Frags<Cfg>& f) {
+  using T = typename Cfg::elem;
+#pragma unroll
+  for (int bm = 0; bm < Cfg::TM; ++bm)
+    f.a[bm] = read_frag<T, typename Cfg::LA, Cfg::A_KMAJOR>(stage, wm * Cfg::WTM + bm * 32, g);
+#pragma unroll
+  for (int bn = 0; bn < Cfg::TN; ++bn)
+    f.b[bn] = read_frag<T, typename Cfg::LB, Cfg::B_KMAJOR>(stage + Cfg::A_BYTES,
+                                                            wn * Cfg::WTN + bn * 32, g);
+}
+
+template <class Cfg>
+__device__ __forceinline__ void mma_group(const Frags<Cfg>& f, f32x16 (&acc)[Cfg::TM][Cfg::TN]) {
+  using T = typename Cfg::elem;
+#pragma unroll
+  for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+    for (int bn = 0; bn < Cfg::TN; ++bn) mfma_group<T>(f.a[bm], f.b[bn], acc[bm][bn]);
+}
+
+constexpr int kGroups = kSlabBytes / 32;   // reduction groups (fragment reads) per slab
+
+// Groups 0 .. kGroups-2 of the slab in `stage`: the fragments of group g+1 are read while the
+// MFMAs of group g run.  On entry fc holds group 0; on exit it holds the last group, not yet
+// multiplied.
+template <class Cfg>
+__device__ __forceinline__ void mma_slab_head(const char* stage, int wm, int wn, Frags<Cfg>& fc,
+                                              f32x16 (&acc)[Cfg::TM][Cfg::TN]) {
+#pragma unroll
+  for (int g = 0; g + 1 < kGroups; ++g) {
+    Frags<Cfg> fn;
+    read_group<Cfg>(stage, g + 1, wm, wn, fn);
+    __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs they do not feed
+    mma_group<Cfg>(fc, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    fc = fn;
+  }
+}
+
 // Accumulate acc += A_tile * B_tile^T over `nslabs` slabs of K.
 //   A: element (first of this workgroup's BM tile rows, first reduction step of its range)
 //   B: likewise for its BN tile rows;  lda / ldb in elements.
 //   smem: Cfg::LDS_BYTES bytes, 16-byte aligned.  Ends with a barrier (smem may be reused).
+// Software pipeline, three levels deep:
+//   * two LDS stages and two register sets: while slab s is multiplied out of LDS, slab s+1 sits
+//     in one register set (stored to the other stage at the end of the iteration) and slab s+2 is
+//     in flight into the other set, so a global load has two iterations to arrive;
+//   * inside a slab the fragments of group g+1 are read from LDS while group g is multiplied;
+//   * the last group of a slab is multiplied AFTER the barrier, behind the first fragment reads
+//     of the next slab, so the LDS latency at the slab boundary is covered as well.
 template <class Cfg>
 __device__ __forceinline__ void gemm_tile(const typename Cfg::elem* __restrict__ A, int64_t lda,
                                           const typename Cfg::elem* __restrict__ B, int64_t ldb,
@@ -179,46 +250,97 @@ __device__ __forceinline__ void gemm_tile(const typename Cfg::elem* __restrict__
   const int wave = threadIdx.x >> 6;
   const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
 
-  Stager<T, LA, Cfg::THREADS, Cfg::A_CHUNKS, Cfg::A_KMAJOR> sa;
-  Stager<T, LB, Cfg::THREADS, Cfg::B_CHUNKS, Cfg::B_KMAJOR> sb;
+  typedef Stager<T, LA, Cfg::THREADS, Cfg::A_CHUNKS, Cfg::A_KMAJOR> SA;
+  typedef Stager<T, LB, Cfg::THREADS, Cfg::B_CHUNKS, Cfg::B_KMAJOR> SB;
+  SA sa;
+  SB sb;
   sa.init(A, lda);
   sb.init(B, ldb);
-  u32x4 ra[Cfg::A_CHUNKS], rb[Cfg::B_CHUNKS];
-  sa.load(0, ra);
-  sb.load(0, rb);
-  sa.store(smem, ra);
-  sb.store(smem + Cfg::A_BYTES, rb);
-  __syncthreads();
-
-  constexpr int GROUPS = kSlabBytes / 32;   // fragment groups per slab
-  for (int s = 0; s < nslabs; ++s) {
-    const char* cur = smem + (s & 1) * Cfg::STAGE_BYTES;
-    char* nxt = smem + ((s + 1) & 1) * Cfg::STAGE_BYTES;
-    const bool more = (s + 1 < nslabs);
-    if (more) {
-      sa.load(s + 1, ra);
-      sb.load(s + 1, rb);
-    }
-#pragma unroll
-    for (int g = 0; g < GROUPS; ++g) {
-      u32x4 fa[Cfg::TM], fb[Cfg::TN];
-#pragma unroll
-      for (int bm = 0; bm < Cfg::TM; ++bm)
-        fa[bm] = read_frag<T, LA, Cfg::A_KMAJOR>(cur, wm * Cfg::WTM + bm * 32, g);
-#pragma unroll
-      for (int bn = 0; bn < Cfg::TN; ++bn)
-        fb[bn] = read_frag<T, LB, Cfg::B_KMAJOR>(cur + Cfg::A_BYTES, wn * Cfg::WTN + bn * 32, g);
-#pragma unroll
-      for (int bm = 0; bm < Cfg::TM; ++bm)
-#pragma unroll
-        for (int bn = 0; bn < Cfg::TN; ++bn) mfma_group<T>(fa[bm], fb[bn], acc[bm][bn]);
-    }
-    if (more) {
-      sa.store(nxt, ra);
-      sb.store(nxt + Cfg::A_BYTES, rb);
-    }
+  char* st0 = smem;
+  char* st1 = smem + Cfg::STAGE_BYTES;
+  const int last = nslabs - 1;
+  Frags<Cfg> fc;
+  if constexpr (Cfg::DIST == 2) {
+    typename SA::Regs a0 = {}, a1 = {};
+    typename SB::Regs b0 = {}, b1 = {};
+    a0 = sa.load(0);
+    b0 = sb.load(0);
+    a1 = sa.load(last < 1 ? last : 1);
+    b1 = sb.load(last < 1 ? last : 1);
+    sa.store(st0, a0);
+    sb.store(st0 + Cfg::A_BYTES, b0);
+    a0 = sa.load(last < 2 ? last : 2);
+    b0 = sb.load(last < 2 ? last : 2);
     __syncthreads();
+    read_group<Cfg>(st0, 0, wm, wn, fc);
+    // Invariant at the top of iteration s (even): stage 0 holds slab s, set 1 holds slab s+1,
+    // set 0 holds slab s+2, fc holds group 0 of slab s.  Slab numbers past the end are clamped to
+    // the last slab: such loads, LDS stores and fragment reads are redundant but in bounds, and
+    // keep the loop body free of branches.
+    int s = 0;
+    for (; s + 1 < nslabs; s += 2) {
+      mma_slab_head<Cfg>(st0, wm, wn, fc, acc);
+      sa.store(st1, a1);
+      sb.store(st1 + Cfg::A_BYTES, b1);
+      a1 = sa.load(s + 3 < last ? s + 3 : last);
+      b1 = sb.load(s + 3 < last ? s + 3 : last);
+      __syncthreads();
+      {
+        Frags<Cfg> fn;
+        read_group<Cfg>(st1, 0, wm, wn, fn);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_group<Cfg>(fc, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        fc = fn;
+      }
+      mma_slab_head<Cfg>(st1, wm, wn, fc, acc);
+      sa.store(st0, a0);
+      sb.store(st0 + Cfg::A_BYTES, b0);
+      a0 = sa.load(s + 4 < last ? s + 4 : last);
+      b0 = sb.load(s + 4 < last ? s + 4 : last);
+      __syncthreads();
+      {
+        Frags<Cfg> fn;
+        read_group<Cfg>(st0, 0, wm, wn, fn);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_group<Cfg>(fc, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        fc = fn;
+      }
+    }
+    if (s < nslabs) {   // odd count: the last slab sits in stage 0 and fc holds its group 0
+      mma_slab_head<Cfg>(st0, wm, wn, fc, acc);
+      mma_group<Cfg>(fc, acc);
+    }
+  } else {
+    // One register set: the loads of slab s+1 are issued before slab s is multiplied and stored
+    // to the other stage behind it.
+    typename SA::Regs a0 = {};
+    typename SB::Regs b0 = {};
+    a0 = sa.load(0);
+    b0 = sb.load(0);
+    sa.store(st0, a0);
+    sb.store(st0 + Cfg::A_BYTES, b0);
+    __syncthreads();
+    read_group<Cfg>(st0, 0, wm, wn, fc);
+    for (int s = 0; s < nslabs; ++s) {
+      char* cur = (s & 1) ? st1 : st0;
+      char* nxt = (s & 1) ? st0 : st1;
+      a0 = sa.load(s + 1 < last ? s + 1 : last);
+      b0 = sb.load(s + 1 < last ? s + 1 : last);
+      mma_slab_head<Cfg>(cur, wm, wn, fc, acc);
+      sa.store(nxt, a0);
+      sb.store(nxt + Cfg::A_BYTES, b0);
+      __syncthreads();
+      Frags<Cfg> fn;
+      read_group<Cfg>(nxt, 0, wm, wn, fn);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_group<Cfg>(fc, acc);
+      __builtin_amdgcn_sched_barrier(0);
+      fc = fn;
+    }
   }
+  __syncthreads();
 }
 
 template <class Cfg>
