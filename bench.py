@@ -88,6 +88,10 @@ def main() -> int:
     dX = torch.zeros((wl.B, wl.D), dtype=torch.float32, device=dev)
     dW = torch.zeros((cap, wl.D), dtype=torch.float32, device=dev)
 
+    # One plain element-wise pass of known size (reads and writes k*D*4 bytes), untimed: it is the
+    # reference that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run.
+    torch.mul(dW, 1.0, out=dW)
+
     def step(t: int) -> int:
         k = ctx.pfc_sample(labels[t], wl.r, wl.seed, t, idx, yl)
         ctx.pfc_forward_backward(feats[t], Wd, idx, k, yl, wl.s, wl.m, loss, dX, dW)
