@@ -178,10 +178,15 @@ def main() -> int:
     roofline["ms"] = kernels[dominant]["ms"]
     roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant))
 
-    if cpu_baseline is not None:
-        # parity spot check of the run itself: loss of step 0 from a fresh state is not
-        # available any more (state has advanced); the tests cover parity.  Report only.
-        pass
+    # what this GPU sustains on a plain stream copy (k*D*4 bytes each way) and a bare MFMA loop
+    scratch = torch.empty_like(dW)
+    measured = {
+        "stream_copy_GBps": round(ctx.pfc_probe_stream_copy(dW, scratch, 10), 1),
+        "mfma_bf16_TFLOPps": round(ctx.pfc_probe_mfma_bf16(5), 1),
+    }
+    del scratch
+    ref = measured["stream_copy_GBps"] if roofline["bound"] == "hbm" else measured["mfma_bf16_TFLOPps"]
+    roofline["frac_of_measured_peak"] = round(roofline["achieved"] / ref, 4)
 
     out = {
         "metric": "PFC fwd+bwd+update samples/s",
@@ -202,6 +207,7 @@ def main() -> int:
                    "B": wl.B, "D": wl.D, "N": wl.N, "r": wl.r, "k": k},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "measured_peaks": measured,
         "kernels": kernels,
         "kernel_sum_ms": round(sum(kern_ms.values()), 4),
         "final_loss": float(loss.item()),

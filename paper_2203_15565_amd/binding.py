@@ -24,7 +24,7 @@ PRECISION_BF16 = 1
 EXPORTS = [
     "pfc_create", "pfc_destroy", "pfc_num_sampled", "pfc_sample", "pfc_sample_masked",
     "pfc_forward_backward", "pfc_update", "pfc_check", "pfc_set_timing", "pfc_get_timing",
-    "pfc_strerror", "pfc_last_hip_error",
+    "pfc_strerror", "pfc_last_hip_error", "pfc_probe_stream_copy", "pfc_probe_mfma_bf16",
 ]
 
 _lib: Optional[ctypes.CDLL] = None
@@ -73,6 +73,10 @@ def load() -> ctypes.CDLL:
     lib.pfc_set_timing.restype = c.c_int
     lib.pfc_get_timing.argtypes = [vp, c.POINTER(c.c_char_p), c.POINTER(f32), i32]
     lib.pfc_get_timing.restype = c.c_int
+    lib.pfc_probe_stream_copy.argtypes = [vp, vp, vp, i64, i32, c.POINTER(f64)]
+    lib.pfc_probe_stream_copy.restype = c.c_int
+    lib.pfc_probe_mfma_bf16.argtypes = [vp, i32, c.POINTER(f64)]
+    lib.pfc_probe_mfma_bf16.restype = c.c_int
     lib.pfc_strerror.argtypes = [c.c_int]
     lib.pfc_strerror.restype = c.c_char_p
     lib.pfc_last_hip_error.argtypes = []
@@ -160,6 +164,24 @@ class Context:
         rc = load().pfc_set_timing(self._h, 1 if enabled else 0)
         if rc != PFC_OK:
             raise PfcError(rc, "pfc_set_timing")
+
+    def pfc_probe_stream_copy(self, src, dst, reps: int = 10) -> float:
+        """GB/s (read + write) of a plain copy of src into dst (same-size device tensors)."""
+        out = ctypes.c_double(0.0)
+        nbytes = src.numel() * src.element_size()
+        rc = load().pfc_probe_stream_copy(self._h, _ptr(src), _ptr(dst), nbytes, reps,
+                                          ctypes.byref(out))
+        if rc != PFC_OK:
+            raise PfcError(rc, "pfc_probe_stream_copy")
+        return float(out.value)
+
+    def pfc_probe_mfma_bf16(self, reps: int = 5) -> float:
+        """TFLOP/s of a bare bf16 MFMA issue loop."""
+        out = ctypes.c_double(0.0)
+        rc = load().pfc_probe_mfma_bf16(self._h, reps, ctypes.byref(out))
+        if rc != PFC_OK:
+            raise PfcError(rc, "pfc_probe_mfma_bf16")
+        return float(out.value)
 
     def pfc_get_timing(self) -> dict:
         cap = 64

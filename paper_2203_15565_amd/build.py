@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpfc.so")
-SOURCES = ["pfc_api.hip", "pfc_sample.hip", "pfc_fwd_bwd.hip", "pfc_update.hip"]
+SOURCES = ["pfc_api.hip", "pfc_sample.hip", "pfc_fwd_bwd.hip", "pfc_update.hip", "pfc_probe.hip"]
 
 # -packed-fp32-ops off: the compiler must not form v_pk_*_f32 from ordinary float code.
 HIPCC_FLAGS = [

@@ -209,3 +209,73 @@ def test_medium_workload_ten_steps():
 
 def test_large_workload_steps():
     _run_steps(workloads.CONFIGS["large"], 3, check_every_step=False)
+
+
+def _device_weight(wl):
+    """Upload the workload's initial centers chunk by chunk (host never holds all of W)."""
+    torch = _torch()
+    Wd = torch.empty((wl.N, wl.D), dtype=torch.float32, device="cuda")
+    for row0, chunk in workloads.weight_chunks(wl):
+        Wd[row0:row0 + chunk.shape[0]].copy_(torch.from_numpy(chunk))
+    return Wd
+
+
+@pytest.mark.parametrize("name,r", [("headline", 0.1), ("headline", 0.05)])
+def test_full_size_step(name, r):
+    """One whole step at the full class count, in the launch configuration bench.py times.
+    The oracle runs on the sampled rows W[idx] only (the method never reads the others); rows
+    outside idx are compared bit for bit on the device."""
+    torch = _torch()
+    wl = workloads.CONFIGS[name].with_(r=r)
+    Wd = _device_weight(wl)
+    W_before = Wd.clone()
+    vd = torch.zeros_like(Wd)
+    ctx = binding.Context(wl.N, wl.D, wl.B, wl.r, wl.precision)
+    cap = binding.pfc_num_sampled(wl.N, wl.B, wl.r)
+    idx_d = torch.zeros(cap, dtype=torch.int32, device="cuda")
+    yl_d = torch.zeros(wl.B, dtype=torch.int32, device="cuda")
+    loss_d = torch.zeros(1, device="cuda")
+    dX_d = torch.zeros(wl.B, wl.D, device="cuda")
+    dW_d = torch.zeros(cap, wl.D, device="cuda")
+    X = workloads.make_features(wl, 0)
+    labels = workloads.make_labels(wl, 0)
+    labels_d = torch.from_numpy(labels).cuda()
+    X_d = torch.from_numpy(X).cuda()
+    _say("full size step", name, r)
+    k = ctx.pfc_sample(labels_d, wl.r, wl.seed, 0, idx_d, yl_d)
+    ctx.pfc_forward_backward(X_d, Wd, idx_d, k, yl_d, wl.s, wl.m, loss_d, dX_d, dW_d)
+    torch.cuda.synchronize()
+    dWn_g = dW_d[:k].cpu().numpy()
+    ctx.pfc_update(Wd, vd, idx_d, k, dW_d, wl.lr, wl.mu)
+    torch.cuda.synchronize()
+    assert ctx.pfc_check() == binding.PFC_OK
+
+    oidx, oyl, ok = O.sample(labels, wl.N, wl.r, wl.seed, 0)
+    assert k == ok and np.array_equal(idx_d[:k].cpu().numpy(), oidx)
+    assert np.array_equal(yl_d.cpu().numpy(), oyl)
+    sel = torch.from_numpy(oidx.astype(np.int64)).cuda()
+    W_S = W_before[sel].cpu().numpy()
+    o = O.forward_backward(X, W_S, oyl, wl.s, wl.m)
+    gl = float(loss_d.item())
+    _say("   loss", gl, o["loss"])
+    assert abs(gl - o["loss"]) <= LOSS_TOL[wl.precision] * abs(o["loss"])
+    assert rel_max(dX_d.cpu().numpy(), o["dX"]) <= GRAD_TOL[wl.precision]
+    assert rel_max(dWn_g, o["dWn"]) <= GRAD_TOL[wl.precision]
+    # positive rows separately: their gradient is dominated by the fp32 label column
+    prow = np.unique(oyl)
+    assert rel_max(dWn_g[prow], o["dWn"][prow]) <= 1e-3
+    W_S64 = W_S.astype(np.float64)
+    v_S64 = np.zeros_like(W_S64)
+    O.update(W_S64, v_S64, np.arange(k), o["dW"], wl.lr, wl.mu)
+    err = row_rel_err(Wd[sel].cpu().numpy(), W_S64, np.linalg.norm(W_S64, axis=1))
+    _say("   W row err", err)
+    assert err <= W_TOL
+    assert rel_max(vd[sel].cpu().numpy(), v_S64) <= GRAD_TOL[wl.precision]
+    # unsampled rows: bit-identical W, untouched (zero) v -- checked on the device
+    mask = torch.ones(wl.N, dtype=torch.bool, device="cuda")
+    mask[sel] = False
+    same = (Wd.view(torch.int32) == W_before.view(torch.int32)).all(dim=1)
+    assert bool(same[mask].all())
+    assert not bool(vd[mask].any())
+    assert not bool(same[~mask].all())       # and the sampled rows did move
+    ctx.close()
