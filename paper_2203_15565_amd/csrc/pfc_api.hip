@@ -19,7 +19,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "sample_init",   "sample_mark",  "sample_hist0", "sample_scan0", "sample_hist1",
     "sample_scan1",  "sample_hist2", "sample_scan2", "sample_count", "sample_blkscan",
     "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_logits",
-    "row_combine",   "loss_reduce",  "make_xs",      "gemm_dweight", "dweight_label",
+    "row_combine",   "gemm_dweight", "dweight_label",
     "gemm_dfeatures", "dfeatures_final", "update"};
 
 static int64_t ceil_rN(int64_t N, double r) { return (int64_t)ceil(r * (double)N); }
@@ -110,7 +110,7 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
 #define ALLOC(field, bytes)                                  \
   if (rc == PFC_OK) rc = dev_alloc((void**)&c->field, (bytes))
   ALLOC(pos_bits, ((size_t)(N + 31) / 32 + 64) * 4);
-  ALLOC(hist, 3 * 2048 * 4);
+  ALLOC(hist, 3 * 4096 * 4);
   ALLOC(sel, sizeof(SelState));
   ALLOC(blk_cnt, (size_t)c->nblk_cap * 2 * 4);
   ALLOC(blk_off, (size_t)c->nblk_cap * 2 * 4);

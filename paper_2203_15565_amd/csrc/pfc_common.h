@@ -36,8 +36,6 @@ enum KernelId {
   KID_GATHER_W,
   KID_GEMM_LOGITS,
   KID_ROW_COMBINE,
-  KID_LOSS_REDUCE,
-  KID_MAKE_XS,
   KID_GEMM_DW,
   KID_DW_LABEL,
   KID_GEMM_DX,
@@ -74,7 +72,7 @@ struct pfc_ctx {
 
   // sampler scratch
   uint32_t* pos_bits;     // ceil(N/32) words (+ slack): bit j set <=> class j is in the batch
-  uint32_t* hist;         // 3 x 2048 bins
+  uint32_t* hist;         // 3 x 4096 bins (radix passes of 8, 12 and 12 bits)
   pfc::SelState* sel;
   uint32_t* blk_cnt;      // 2 x nblk: per block (#sure, #equal-to-threshold)
   uint32_t* blk_off;      // 2 x nblk: per block (output offset, #equal before)
@@ -89,7 +87,7 @@ struct pfc_ctx {
   void* Wn;        // [kp x D]   normalised sampled centers
   float* rnormW;   // [kp]
   void* E;         // [Bp x kp]  exp(z), label column zeroed
-  float* rowpart;  // [tiles_j x Bp] partial row sums of exp(z)
+  float* rowpart;  // [Bp x tiles_j] partial row sums of exp(z)
   float* clabel;   // [Bp] cosine of the label column
   float* rowscale; // [Bp] s/(B*l_i)
   float* dlabel;   // [Bp] (s/B)(p_iy - 1) rho_i

@@ -6,13 +6,12 @@
 //   normalize_x        Xn = x/|x|                                   (HBM bound, tiny)
 //   gather_normalize_w Wn = W[idx]/|W[idx]|                         (HBM bound)
 //   gemm_logits        c = Wn Xn^T, margin, e = exp(s c) -> E and per-tile row sums (MFMA)
-//   row_combine        l_i, lse_i, per-row loss, s/(B l_i), label-column coefficient
-//   loss_reduce        mean loss
-//   make_xs            Xs = (s/(B l_i)) xn_i
+//   row_combine        l_i, lse_i, per-row loss, s/(B l_i), label-column coefficient,
+//                      Xs = (s/(B l_i)) xn_i
 //   gemm_dweight       dWn = E^T Xs  (off-label part)                (MFMA)
 //   dweight_label      adds the label-column term to the rows of positive classes (fp32)
 //   gemm_dfeatures     partial sums of E Wn over slices of S         (MFMA, split over S)
-//   dfeatures_final    reduce slices, scale, label term, project through x -> x/|x|
+//   dfeatures_final    reduce slices, scale, label term, project through x -> x/|x|; mean loss
 //
 // Because cosines lie in [-1,1] and s <= 64, exp(s c) lies in [e^-64, e^64] and a row sum over
 // at most 2^31 classes stays below 3.4e38: exp needs no running maximum, and one fixed
@@ -278,7 +277,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
     float v = 0.f;
 #pragma unroll
     for (int w = 0; w < Cfg::WM; ++w) v += red[w * Cfg::BN + t];
-    rowpart[(int64_t)tj * Bp + i0 + t] = v;
+    rowpart[(int64_t)(i0 + t) * tiles_j + tj] = v;
   }
   if constexpr (kStage) {
     // one wavefront instruction stores one whole row of the tile: BM * 2 bytes, 8 per lane
@@ -291,81 +290,59 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// row_combine: l_i = sum over tiles (fixed order), then the per-row scalars.
-// Block = 32 rows x 32 partial summers.
+// row_combine: one wavefront per (padded) sample.  l_i = sum of the per-tile partial sums (lane
+// strided, then a fixed shuffle tree: the same order on every run), the per-row scalars, and the
+// row of Xs = (s/(B l_i)) * x_i/|x_i| that feeds the dweight GEMM (zero for padded rows).
 // ---------------------------------------------------------------------------------------------
+template <typename T, int NC>
 __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_j, int B, int Bp,
+                                   int D, const float* __restrict__ X,
+                                   const float* __restrict__ rnormX,
                                    const float* __restrict__ clabel, float s, float cos_m,
                                    float sin_m, float* __restrict__ rowscale,
-                                   float* __restrict__ dlabel, float* __restrict__ lossrow) {
-  __shared__ float sm[32][33];
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-  const int i = blockIdx.x * 32 + tx;
-  float v = 0.f;
-  if (i < Bp)
-    for (int t = ty; t < tiles_j; t += 32) v += rowpart[(int64_t)t * Bp + i];
-  sm[ty][tx] = v;
-  __syncthreads();
-  if (ty == 0 && i < Bp) {
+                                   float* __restrict__ dlabel, float* __restrict__ lossrow,
+                                   T* __restrict__ Xs) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= Bp) return;
+  float scale = 0.f;
+  if (i < B) {
     float l = 0.f;
-    for (int t = 0; t < 32; ++t) l += sm[t][tx];
-    if (i < B) {
+    for (int t = lane; t < tiles_j; t += 64) l += rowpart[(int64_t)i * tiles_j + t];
+    l = wave_sum(l);
+    scale = s / ((float)B * l);
+    if (lane == 0) {
       const float c = clabel[i];
       const float sin2 = 1.f - c * c;
       const float zlab = s * (c * cos_m - sqrtf(fmaxf(sin2, 0.f)) * sin_m);
-      const float lse = logf(l);
       const float p = __expf(zlab) / l;
       const float rho = cos_m + c * sin_m / sqrtf(fmaxf(sin2, kEpsSin2));
-      const float invB = 1.f / (float)B;
-      lossrow[i] = lse - zlab;
-      rowscale[i] = s * invB / l;
-      dlabel[i] = s * invB * (p - 1.f) * rho;
-    } else {
-      lossrow[i] = 0.f;
-      rowscale[i] = 0.f;
-      dlabel[i] = 0.f;
+      lossrow[i] = logf(l) - zlab;
+      rowscale[i] = scale;
+      dlabel[i] = (s / (float)B) * (p - 1.f) * rho;
     }
+  } else if (lane == 0) {
+    lossrow[i] = 0.f;
+    rowscale[i] = 0.f;
+    dlabel[i] = 0.f;
   }
-}
-
-__global__ void loss_reduce_kernel(const float* __restrict__ lossrow, int B,
-                                   float* __restrict__ loss_out) {
-  __shared__ float sm[256];
-  float v = 0.f;
-  for (int i = threadIdx.x; i < B; i += 256) v += lossrow[i];
-  sm[threadIdx.x] = v;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) loss_out[0] = sm[0] / (float)B;
-}
-
-// Xs[i][d] = (s/(B l_i)) * x_i[d]/|x_i| (zero rows for padded i).
-template <typename T>
-__global__ void make_xs_kernel(const float* __restrict__ X, int B, int Bp, int D,
-                               const float* __restrict__ rnormX,
-                               const float* __restrict__ rowscale, T* __restrict__ Xs) {
-  const int64_t e4 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // group of 4 elements
-  const int64_t total = (int64_t)Bp * D / 4;
-  if (e4 >= total) return;
-  const int i = (int)(e4 * 4 / D);
-  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (i < B) {
-    v = *reinterpret_cast<const float4*>(X + e4 * 4);
-    const float f = rnormX[i] * rowscale[i];
-    v.x *= f; v.y *= f; v.z *= f; v.w *= f;
-  }
-  T o[4] = {from_float<T>(v.x), from_float<T>(v.y), from_float<T>(v.z), from_float<T>(v.w)};
-  if constexpr (sizeof(T) == 2) {
-    uint2 pk;
-    __builtin_memcpy(&pk, o, 8);
-    *reinterpret_cast<uint2*>(Xs + e4 * 4) = pk;
-  } else {
-    uint4 pk;
-    __builtin_memcpy(&pk, o, 16);
-    *reinterpret_cast<uint4*>(Xs + e4 * 4) = pk;
+  const float f = (i < B) ? rnormX[i] * scale : 0.f;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int d = c * 256 + lane * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < B) v = *reinterpret_cast<const float4*>(X + (int64_t)i * D + d);
+    T o[4] = {from_float<T>(v.x * f), from_float<T>(v.y * f), from_float<T>(v.z * f),
+              from_float<T>(v.w * f)};
+    if constexpr (sizeof(T) == 2) {
+      uint2 pk;
+      __builtin_memcpy(&pk, o, 8);
+      *reinterpret_cast<uint2*>(Xs + (int64_t)i * D + d) = pk;
+    } else {
+      uint4 pk;
+      __builtin_memcpy(&pk, o, 16);
+      *reinterpret_cast<uint4*>(Xs + (int64_t)i * D + d) = pk;
+    }
   }
 }
 
@@ -521,8 +498,24 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
                                        const float* __restrict__ rnormX,
                                        const float* __restrict__ rnormW,
                                        const float* __restrict__ rowscale,
-                                       const float* __restrict__ dlabel, float* __restrict__ dX) {
+                                       const float* __restrict__ dlabel, float* __restrict__ dX,
+                                       const float* __restrict__ lossrow,
+                                       float* __restrict__ loss_out) {
   const int lane = threadIdx.x & 63;
+  if (blockIdx.x == gridDim.x - 1) {
+    // the extra last block: mean loss, summed in a fixed order (strided partials, then a tree)
+    __shared__ float sm[256];
+    float v = 0.f;
+    for (int r = threadIdx.x; r < B; r += 256) v += lossrow[r];
+    sm[threadIdx.x] = v;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+      if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) loss_out[0] = sm[0] / (float)B;
+    return;
+  }
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (i >= B) return;
   constexpr int nchunk = NC;
@@ -608,14 +601,11 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     PFC_LAUNCH(c, KID_GEMM_LOGITS, gemm_logits_kernel<CfgF>, dim3(xcd_grid(tiles_i, tiles_j)),
                dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, Bp, kp, yl, s, cos_m, sin_m,
                E, c->rowpart, c->clabel, tiles_j, tiles_i);
-    PFC_LAUNCH(c, KID_ROW_COMBINE, row_combine_kernel, dim3((Bp + 31) / 32), dim3(1024), 0,
-               c->rowpart, tiles_j, B, Bp, c->clabel, s, cos_m, sin_m, c->rowscale, c->dlabel,
-               c->lossrow);
+    auto combine_kernel = row_combine_kernel<T, NC>;
+    PFC_LAUNCH(c, KID_ROW_COMBINE, combine_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowpart,
+               tiles_j, B, Bp, D, X, c->rnormX, c->clabel, s, cos_m, sin_m, c->rowscale, c->dlabel,
+               c->lossrow, Xs);
   }
-  PFC_LAUNCH(c, KID_LOSS_REDUCE, loss_reduce_kernel, dim3(1), dim3(256), 0, c->lossrow, B,
-             loss_out);
-  PFC_LAUNCH(c, KID_MAKE_XS, make_xs_kernel<T>, dim3((unsigned)(((int64_t)Bp * D / 4 + 255) / 256)),
-             dim3(256), 0, X, B, Bp, D, c->rnormX, c->rowscale, Xs);
   {
     const int tiles_j = (int)(kp / CfgW::BM), tiles_d = D / CfgW::BN;
     PFC_LAUNCH(c, KID_GEMM_DW, gemm_dweight_kernel<CfgW>, dim3(xcd_grid(tiles_d, tiles_j)),
@@ -638,9 +628,9 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                dim3(xcd_grid(tiles_i * tiles_d, splits)), dim3(CfgX::THREADS), CfgX::LDS_BYTES, E,
                Wn, D, Bp, kp, slabs_total, slabs_per, splits, c->dXpart, tiles_i, tiles_d);
   }
-  PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3((B + 3) / 4), dim3(256), 0,
+  PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3((B + 3) / 4 + 1), dim3(256), 0,
              c->dXpart, splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW,
-             c->rowscale, c->dlabel, dX_out);
+             c->rowscale, c->dlabel, dX_out, c->lossrow, loss_out);
   return PFC_OK;
 }
 

@@ -4,7 +4,7 @@
 // Integer work only.  Every class gets a 32-bit Philox4x32-10 score (Salmon et al., SC'11),
 // recomputed wherever it is needed (about 60 integer operations per four classes; nothing is
 // stored per class except one "is in the batch" bit).  The k - U negatives with the largest
-// scores are found by a three-pass radix select (11 + 11 + 10 bits), equal scores going to the
+// scores are found by a three-pass radix select (8 + 12 + 12 bits), equal scores going to the
 // smaller class id; an index-ordered compaction then writes S in ascending class id.
 #include <math.h>
 
@@ -17,6 +17,15 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kClassesPerBlock = 2048;                 // ordered passes: 2 x (256 threads x 4)
 constexpr int kItersPerBlock = kClassesPerBlock / (kThreads * 4);
+
+// Radix passes over the 32-bit score: bits [31:24], [23:12], [11:0].  The first pass sees every
+// class, so it is kept narrow (256 bins: few global atomics per block); the later passes see
+// only the classes inside the chosen bin, so their 4096-bin histograms are almost empty.
+constexpr int kHistStride = 4096;
+template <int P> struct Pass;
+template <> struct Pass<0> { static constexpr int kBins = 256, kShift = 24; };
+template <> struct Pass<1> { static constexpr int kBins = 4096, kShift = 12; };
+template <> struct Pass<2> { static constexpr int kBins = 4096, kShift = 0; };
 
 struct PhiloxKey {
   uint32_t k0, k1;   // lo32(seed), hi32(seed)
@@ -51,7 +60,7 @@ __global__ void sample_init_kernel(uint32_t* __restrict__ pos_bits, int64_t nwor
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = t; i < nwords; i += stride) pos_bits[i] = 0u;
-  for (int64_t i = t; i < 3 * 2048; i += stride) hist[i] = 0u;
+  for (int64_t i = t; i < 3 * kHistStride; i += stride) hist[i] = 0u;
   if (t < (int64_t)(sizeof(SelState) / 4)) reinterpret_cast<uint32_t*>(sel)[t] = 0u;
 }
 
@@ -67,14 +76,15 @@ __global__ void sample_mark_kernel(const int64_t* __restrict__ labels, int B, in
   atomicOr(&pos_bits[y >> 5], 1u << (y & 31));
 }
 
-// Radix pass P over the non-positive classes whose score agrees with the prefix found so far.
-// P = 0: bins = bits 31..21; also counts the positives.  P = 1: bits 20..10.  P = 2: bits 9..0.
+// Radix pass P over the non-positive classes whose score agrees with the prefix found so far;
+// pass 0 also counts the positives.
 template <int P>
 __global__ void sample_hist_kernel(int64_t N, PhiloxKey key, const uint32_t* __restrict__ pos_bits,
                                    uint32_t* __restrict__ hist, SelState* __restrict__ sel) {
-  __shared__ uint32_t lh[2048];
+  constexpr int kBins = Pass<P>::kBins, kShift = Pass<P>::kShift;
+  __shared__ uint32_t lh[kBins];
   __shared__ uint32_t lpos;
-  for (int b = threadIdx.x; b < 2048; b += blockDim.x) lh[b] = 0u;
+  for (int b = threadIdx.x; b < kBins; b += blockDim.x) lh[b] = 0u;
   if (threadIdx.x == 0) lpos = 0u;
   __syncthreads();
   uint32_t prefix = 0u, none = 0u;
@@ -95,20 +105,21 @@ __global__ void sample_hist_kernel(int64_t N, PhiloxKey key, const uint32_t* __r
         const int64_t j = (int64_t)q * 4 + e;
         if (j >= N || ((pb >> e) & 1u)) continue;
         if (P == 0) {
-          atomicAdd(&lh[u[e] >> 21], 1u);
-        } else if (P == 1) {
-          if ((u[e] >> 21) == (prefix >> 21)) atomicAdd(&lh[(u[e] >> 10) & 2047u], 1u);
+          atomicAdd(&lh[u[e] >> kShift], 1u);
         } else {
-          if ((u[e] >> 10) == (prefix >> 10)) atomicAdd(&lh[u[e] & 1023u], 1u);
+          // bits above this pass's field must equal the prefix
+          constexpr int kAbove = kShift + 12;
+          if ((u[e] >> kAbove) == (prefix >> kAbove))
+            atomicAdd(&lh[(u[e] >> kShift) & (kBins - 1)], 1u);
         }
       }
     }
     if (P == 0 && npos) atomicAdd(&lpos, npos);
   }
   __syncthreads();
-  for (int b = threadIdx.x; b < 2048; b += blockDim.x) {
+  for (int b = threadIdx.x; b < kBins; b += blockDim.x) {
     const uint32_t c = lh[b];
-    if (c) atomicAdd(&hist[P * 2048 + b], c);
+    if (c) atomicAdd(&hist[P * kHistStride + b], c);
   }
   if (P == 0 && threadIdx.x == 0 && lpos) atomicAdd(&sel->U, lpos);
 }
@@ -137,12 +148,12 @@ __global__ void sample_scan_kernel(const uint32_t* __restrict__ hist, SelState* 
   __syncthreads();
   if (s_none) return;
   const uint32_t need = s_need;
-  constexpr int kBins = (P == 2) ? 1024 : 2048;
+  constexpr int kBins = Pass<P>::kBins;
   constexpr int kPer = kBins / 256;
   // thread t owns the descending bins kBins-1-t*kPer .. kBins-1-(t*kPer+kPer-1)
   uint32_t mine = 0;
 #pragma unroll
-  for (int e = 0; e < kPer; ++e) mine += hist[P * 2048 + (kBins - 1 - (t * kPer + e))];
+  for (int e = 0; e < kPer; ++e) mine += hist[P * kHistStride + (kBins - 1 - (t * kPer + e))];
   // inclusive scan over threads
   uint32_t inc = mine;
   const int lane = t & 63, w = t >> 6;
@@ -161,11 +172,10 @@ __global__ void sample_scan_kernel(const uint32_t* __restrict__ hist, SelState* 
     uint32_t cum = exc;
     for (int e = 0; e < kPer; ++e) {
       const int b = kBins - 1 - (t * kPer + e);
-      const uint32_t c = hist[P * 2048 + b];
+      const uint32_t c = hist[P * kHistStride + b];
       if (cum + c >= need) {
         sel->need = need - cum;   // how many to take from inside this bin
-        const int shift = (P == 0) ? 21 : (P == 1) ? 10 : 0;
-        sel->prefix = sel->prefix | ((uint32_t)b << shift);
+        sel->prefix = sel->prefix | ((uint32_t)b << Pass<P>::kShift);
         break;
       }
       cum += c;
@@ -357,11 +367,11 @@ int sample_impl(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t
   if (nblk > c->nblk_cap) return PFC_EINVAL;
   const int64_t nq = (N + 3) / 4;
   int hist_blocks = (int)((nq + kThreads * 4 - 1) / (kThreads * 4));
-  if (hist_blocks > 2048) hist_blocks = 2048;
+  if (hist_blocks > 512) hist_blocks = 512;
   if (hist_blocks < 1) hist_blocks = 1;
   int init_blocks = (int)((nwords + kThreads - 1) / kThreads);
   if (init_blocks > 1024) init_blocks = 1024;
-  if (init_blocks < 24) init_blocks = 24;   // also covers the 3 x 2048 histogram words
+  if (init_blocks < 48) init_blocks = 48;   // also covers the 3 x 4096 histogram words
 
   PFC_LAUNCH(c, KID_SAMPLE_INIT, sample_init_kernel, dim3(init_blocks), dim3(kThreads), 0,
              c->pos_bits, nwords, c->hist, c->sel);
