@@ -22,9 +22,16 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, GB/s
 PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA
 PEAK_FP32_MFMA_TFLOPS = 157.3  # fp32 MFMA
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
-# (workload, kernel).  None where no counter run has been recorded.
-MEASURED_TRAFFIC_BYTES: dict = {}
+# HBM bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/headline_step_hbm_traffic.md, keyed by (workload, r, kernel).  None where
+# no counter run has been recorded.
+MEASURED_TRAFFIC_BYTES: dict = {
+    ("headline", 0.1, "update"): 2115926703,
+    ("headline", 0.1, "gather_normalize_w"): 635793832,
+    ("headline", 0.1, "gemm_logits"): 775603114,
+    ("headline", 0.1, "gemm_dweight"): 902907272,
+    ("headline", 0.1, "gemm_dfeatures"): 704491005,
+}
 
 
 def algorithmic_work(B: int, D: int, k: int, precision: int) -> dict:
@@ -176,7 +183,7 @@ def main() -> int:
     roofline = {"kernel": dominant}
     roofline.update({f: kernels[dominant][f] for f in ("bound", "achieved", "peak", "unit", "frac")})
     roofline["ms"] = kernels[dominant]["ms"]
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant))
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, wl.r, dominant))
 
     # what this GPU sustains on a plain stream copy (k*D*4 bytes each way) and a bare MFMA loop
     scratch = torch.empty_like(dW)
