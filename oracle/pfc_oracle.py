@@ -12,7 +12,10 @@ What it follows (arXiv 2203.15565, "Partial FC"):
   * Eq. 1: softmax cross entropy, mean over the batch, evaluated over the sampled set S
     only (Eq. 4 restricts the sum to j in S).  The paper trains with the margin-based
     variant (Sec. 4.1, "hyper-parameters of margin-based softmax loss"); the formula is
-    not printed there, so the ArcFace form  s*cos(theta + m)  on the label logit is used.
+    not printed there, so the ArcFace form  s*cos(theta + m)  on the label logit is the
+    default; the CosFace form  s*(cos(theta) - m)  is the option.  Sec. 3.3 / Fig. 4 caption:
+    the PFC* variant filters negatives above a fixed cosine threshold; Sec. 3.3 defines the
+    diagnostics APCS and AMNCS.
   * Eq. 2 / Eq. 4: gradient w.r.t. the feature; Eq. 3: gradient / update of a center.
     They are printed for the plain soft-max; here they are carried through the scale,
     the margin and the two L2 normalisations by the chain rule.
@@ -136,21 +139,33 @@ def sample(labels, N: int, r: float, seed: int, step: int, score_mask: int = 0xF
     return idx, y_local, k
 
 
-def forward_backward(X, W_S, y_local, s: float, m: float):
+def forward_backward(X, W_S, y_local, s: float, m: float, margin: str = "arcface",
+                     filter_threshold=None):
     """Margin-softmax loss over the sampled centers and all its gradients, in fp64.
 
     X: B x D raw features; W_S: k x D raw sampled centers (rows W[idx]); y_local[i] is the
     row of W_S that is sample i's own class.  Follows Eq. 1 (loss, mean over B) with the
-    label logit replaced by s*cos(theta + m), and Eq. 2-4 by the chain rule.
+    label logit replaced by the margin-based one, and Eq. 2-4 by the chain rule.
+
+    margin: "arcface"  label logit s*cos(theta + m)  (additive angular margin), or
+            "cosface"  label logit s*(cos(theta) - m) (additive cosine margin);
+            Sec. 4.1 trains with the hyper-parameters of both papers.
+    filter_threshold: the PFC* variant of Sec. 3.3 / Fig. 4 caption: a NEGATIVE center whose
+            cosine to the sample exceeds the fixed threshold (0.4 in the paper) is left out of that
+            sample's softmax.  None keeps every center.  The mask is a function of the clamped cosine; it is constant in a
+            neighbourhood of almost every input, so it carries no gradient of its own.
 
     Returns a dict:
       loss                      scalar
-      cos (B x k, clamped), z (B x k logits), lse (B), p (B x k)
+      cos (B x k, clamped), z (B x k logits; -inf where filtered), lse (B), p (B x k)
       dc  (B x k)               dL/d cos
       dXn (B x D), dWn (k x D)  gradients w.r.t. the normalised rows
       u (B), t (k)              dXn_i . xn_i  and  dWn_j . wn_j
       dX (B x D), dW (k x D)    gradients w.r.t. the raw rows
       xn, wn, x_norm, w_norm
+      apcs                      mean over the batch of the label cosine        (Sec. 3.3)
+      amncs                     mean over the batch of the largest cosine to a sampled center
+                                other than the label's, taken before any filtering (Sec. 3.3)
     """
     X = np.asarray(X, dtype=np.float64)
     W_S = np.asarray(W_S, dtype=np.float64)
@@ -161,6 +176,8 @@ def forward_backward(X, W_S, y_local, s: float, m: float):
         raise ValueError("shape mismatch")
     if y.min() < 0 or y.max() >= k:
         raise ValueError("y_local outside [0, k)")
+    if margin not in ("arcface", "cosface"):
+        raise ValueError("unknown margin")
     rows = np.arange(B)
 
     x_norm = np.maximum(np.sqrt((X * X).sum(axis=1)), EPS_NORM)
@@ -169,22 +186,32 @@ def forward_backward(X, W_S, y_local, s: float, m: float):
     wn = W_S / w_norm[:, None]
 
     c = np.clip(xn @ wn.T, -1.0, 1.0)
+    onehot = np.zeros((B, k), dtype=bool)
+    onehot[rows, y] = True
     z = s * c
     c_lab = c[rows, y]
-    sin_lab = np.sqrt(1.0 - c_lab * c_lab)
-    z[rows, y] = s * (c_lab * math.cos(m) - sin_lab * math.sin(m))   # s*cos(theta+m)
+    if margin == "arcface":
+        sin_lab = np.sqrt(1.0 - c_lab * c_lab)
+        z[rows, y] = s * (c_lab * math.cos(m) - sin_lab * math.sin(m))   # s*cos(theta+m)
+        # d cos(theta+m) / d cos(theta) = sin(theta+m)/sin(theta)
+        rho = math.cos(m) + c_lab * math.sin(m) / np.sqrt(np.maximum(1.0 - c_lab * c_lab, EPS_SIN2))
+    else:
+        z[rows, y] = s * (c_lab - m)
+        rho = np.ones(B)
+    keep = np.ones((B, k), dtype=bool)
+    if filter_threshold is not None:
+        keep = onehot | ~(c > float(filter_threshold))
+        z = np.where(keep, z, -np.inf)
 
     zmax = z.max(axis=1)
     lse = zmax + np.log(np.exp(z - zmax[:, None]).sum(axis=1))
     loss = float((lse - z[rows, y]).sum() / B)
 
-    p = np.exp(z - lse[:, None])
+    p = np.exp(z - lse[:, None])       # exactly 0 where filtered
     dz = p.copy()
     dz[rows, y] -= 1.0
     dz /= B
     dc = s * dz
-    # d cos(theta+m) / d cos(theta) = sin(theta+m)/sin(theta)
-    rho = math.cos(m) + c_lab * math.sin(m) / np.sqrt(np.maximum(1.0 - c_lab * c_lab, EPS_SIN2))
     dc[rows, y] *= rho
 
     dXn = dc @ wn
@@ -193,8 +220,15 @@ def forward_backward(X, W_S, y_local, s: float, m: float):
     t = (dWn * wn).sum(axis=1)
     dX = (dXn - u[:, None] * xn) / x_norm[:, None]
     dW = (dWn - t[:, None] * wn) / w_norm[:, None]
+
+    apcs = float(c_lab.mean())
+    if k > 1:
+        amncs = float(np.where(onehot, -np.inf, c).max(axis=1).mean())
+    else:
+        amncs = float("nan")
     return dict(loss=loss, cos=c, z=z, lse=lse, p=p, dc=dc, dXn=dXn, dWn=dWn, u=u, t=t,
-                dX=dX, dW=dW, xn=xn, wn=wn, x_norm=x_norm, w_norm=w_norm)
+                dX=dX, dW=dW, xn=xn, wn=wn, x_norm=x_norm, w_norm=w_norm, apcs=apcs, amncs=amncs,
+                keep=keep)
 
 
 def update(W, v, idx, dW, lr: float, mu: float) -> None:
