@@ -108,6 +108,30 @@ int pfc_forward_backward(pfc_ctx* ctx, const float* features, const float* weigh
                          float* loss_out, float* dfeatures_out, float* dweight_out);
 
 /*
+ * pfc_forward_backward_ex -- pfc_forward_backward with the variants the paper also trains with.
+ *   margin_type       PFC_MARGIN_ARCFACE: label logit s*cos(theta + m) (as pfc_forward_backward);
+ *                     PFC_MARGIN_COSFACE: label logit s*(cos(theta) - m).  Sec. 4.1 uses the
+ *                     hyper-parameters of both margin-based losses.
+ *   filter_threshold  the PFC* variant (Sec. 3.3, Fig. 4 caption): a negative center whose clamped
+ *                     cosine to sample i is greater than this value (0.4 in the paper) is left out
+ *                     of sample i's softmax, in the loss and in every gradient.  The label center
+ *                     is never filtered.  Any value >= 1 switches the filter off; values below -1
+ *                     are rejected.
+ *   stats_out         dev, fp32[2] or NULL: {APCS, AMNCS} of Sec. 3.3 -- the batch mean of the label
+ *                     cosine, and the batch mean of the largest cosine between a sample and a
+ *                     sampled center other than its label's (taken before filtering; needs k >= 2).
+ * Everything else is as for pfc_forward_backward, which is this call with PFC_MARGIN_ARCFACE, the
+ * filter off and stats_out = NULL.
+ */
+#define PFC_MARGIN_ARCFACE 0
+#define PFC_MARGIN_COSFACE 1
+int pfc_forward_backward_ex(pfc_ctx* ctx, const float* features, const float* weight,
+                            const int32_t* idx, int64_t k, const int32_t* labels_local, int32_t B,
+                            float s, float m, int32_t margin_type, float filter_threshold,
+                            float* loss_out, float* dfeatures_out, float* dweight_out,
+                            float* stats_out);
+
+/*
  * pfc_update -- SGD with momentum on the sampled rows only (Eq. 3; text after Eq. 4: only the
  * sampled centers are updated in an iteration).  For every j < k, with W_j = weight[idx[j]]:
  *     wn = W_j/|W_j|;  g = (dweight[j] - <dweight[j], wn> wn)/|W_j|

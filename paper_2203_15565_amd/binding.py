@@ -20,10 +20,12 @@ PFC_EHIP = -3
 PFC_ENOMEM = -4
 PRECISION_FP32 = 0
 PRECISION_BF16 = 1
+MARGIN_ARCFACE = 0
+MARGIN_COSFACE = 1
 
 EXPORTS = [
     "pfc_create", "pfc_destroy", "pfc_num_sampled", "pfc_sample", "pfc_sample_masked",
-    "pfc_forward_backward", "pfc_update", "pfc_check", "pfc_set_timing", "pfc_get_timing",
+    "pfc_forward_backward", "pfc_forward_backward_ex", "pfc_update", "pfc_check", "pfc_set_timing", "pfc_get_timing",
     "pfc_strerror", "pfc_last_hip_error", "pfc_probe_stream_copy", "pfc_probe_mfma_bf16",
 ]
 
@@ -65,6 +67,9 @@ def load() -> ctypes.CDLL:
     lib.pfc_sample_masked.restype = c.c_int
     lib.pfc_forward_backward.argtypes = [vp, vp, vp, vp, i64, vp, i32, f32, f32, vp, vp, vp]
     lib.pfc_forward_backward.restype = c.c_int
+    lib.pfc_forward_backward_ex.argtypes = [vp, vp, vp, vp, i64, vp, i32, f32, f32, i32, f32, vp, vp,
+                                            vp, vp]
+    lib.pfc_forward_backward_ex.restype = c.c_int
     lib.pfc_update.argtypes = [vp, vp, vp, vp, i64, vp, f32, f32]
     lib.pfc_update.restype = c.c_int
     lib.pfc_check.argtypes = [vp]
@@ -145,6 +150,17 @@ class Context:
                                          _ptr(loss_out), _ptr(dfeatures_out), _ptr(dweight_out))
         if rc != PFC_OK:
             raise PfcError(rc, "pfc_forward_backward")
+
+    def pfc_forward_backward_ex(self, features, weight, idx, k: int, labels_local, s: float,
+                                m: float, margin_type: int, filter_threshold: float, loss_out,
+                                dfeatures_out, dweight_out, stats_out=None) -> None:
+        rc = load().pfc_forward_backward_ex(self._h, _ptr(features), _ptr(weight), _ptr(idx), k,
+                                            _ptr(labels_local), features.shape[0], s, m,
+                                            margin_type, filter_threshold, _ptr(loss_out),
+                                            _ptr(dfeatures_out), _ptr(dweight_out),
+                                            _ptr(stats_out))
+        if rc != PFC_OK:
+            raise PfcError(rc, "pfc_forward_backward_ex")
 
     def pfc_update(self, weight, momentum, idx, k: int, dweight, lr: float, mu: float) -> None:
         rc = load().pfc_update(self._h, _ptr(weight), _ptr(momentum), _ptr(idx), k, _ptr(dweight),

@@ -66,7 +66,7 @@ int pfc_destroy(pfc_ctx* c) {
   if (!c) return PFC_EINVAL;
   (void)hipStreamSynchronize(c->stream);
   void* bufs[] = {c->pos_bits, c->hist, c->sel, c->blk_cnt, c->blk_off, c->err_flag, c->Xn,
-                  c->Xs, c->rnormX, c->Wn, c->rnormW, c->E, c->rowpart,
+                  c->Xs, c->rnormX, c->Wn, c->rnormW, c->E, c->rowpart, c->rowmaxpart, c->rowmax,
                   c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
@@ -122,6 +122,8 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(rnormW, kp * 4);
   ALLOC(E, Bp * kp * es);
   ALLOC(rowpart, (kp / kPadK) * 2 * Bp * 4);
+  ALLOC(rowmaxpart, (kp / kPadK) * 2 * Bp * 4);
+  ALLOC(rowmax, Bp * 4);
   ALLOC(clabel, Bp * 4);
   ALLOC(rowscale, Bp * 4);
   ALLOC(dlabel, Bp * 4);
@@ -205,15 +207,26 @@ int pfc_sample(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t 
   return pfc_sample_masked(c, labels, B, r, seed, step, 0xFFFFFFFFu, idx_out, yl_out, k_out);
 }
 
-int pfc_forward_backward(pfc_ctx* c, const float* X, const float* W, const int32_t* idx,
-                         int64_t k, const int32_t* yl, int32_t B, float s, float m,
-                         float* loss_out, float* dX_out, float* dW_out) {
+int pfc_forward_backward_ex(pfc_ctx* c, const float* X, const float* W, const int32_t* idx,
+                            int64_t k, const int32_t* yl, int32_t B, float s, float m,
+                            int32_t margin_type, float filter_threshold, float* loss_out,
+                            float* dX_out, float* dW_out, float* stats_out) {
   if (!c || !X || !W || !idx || !yl || !loss_out || !dX_out || !dW_out) return PFC_EINVAL;
   if (B < 1 || B > c->B_max) return PFC_EINVAL;
   if (k < 1 || k > c->k_cap || k > c->N) return PFC_EINVAL;
   if (!(s > 0.f) || !(s <= 64.f)) return PFC_EINVAL;
+  if (margin_type != PFC_MARGIN_ARCFACE && margin_type != PFC_MARGIN_COSFACE) return PFC_EINVAL;
   if (!(m >= 0.f) || !(m < 3.14159265f)) return PFC_EINVAL;
-  return forward_backward_impl(c, X, W, idx, k, yl, B, s, m, loss_out, dX_out, dW_out);
+  if (!(filter_threshold == filter_threshold) || filter_threshold < -1.f) return PFC_EINVAL;
+  return forward_backward_impl(c, X, W, idx, k, yl, B, s, m, margin_type, filter_threshold,
+                               loss_out, dX_out, dW_out, stats_out);
+}
+
+int pfc_forward_backward(pfc_ctx* c, const float* X, const float* W, const int32_t* idx,
+                         int64_t k, const int32_t* yl, int32_t B, float s, float m,
+                         float* loss_out, float* dX_out, float* dW_out) {
+  return pfc_forward_backward_ex(c, X, W, idx, k, yl, B, s, m, PFC_MARGIN_ARCFACE, 2.f, loss_out,
+                                 dX_out, dW_out, nullptr);
 }
 
 int pfc_update(pfc_ctx* c, float* W, float* v, const int32_t* idx, int64_t k, const float* dW,

@@ -88,6 +88,8 @@ struct pfc_ctx {
   float* rnormW;   // [kp]
   void* E;         // [Bp x kp]  exp(z), label column zeroed
   float* rowpart;  // [Bp x tiles_j] partial row sums of exp(z)
+  float* rowmaxpart;  // [Bp x tiles_j] partial row maxima of the non-label cosines (options)
+  float* rowmax;   // [Bp]
   float* clabel;   // [Bp] cosine of the label column
   float* rowscale; // [Bp] s/(B*l_i)
   float* dlabel;   // [Bp] (s/B)(p_iy - 1) rho_i
@@ -142,7 +144,8 @@ int sample_impl(pfc_ctx* ctx, const int64_t* labels, int32_t B, double r, uint64
                 int64_t* k_out);
 int forward_backward_impl(pfc_ctx* ctx, const float* X, const float* W, const int32_t* idx,
                           int64_t k, const int32_t* yl, int32_t B, float s, float m,
-                          float* loss_out, float* dX_out, float* dW_out);
+                          int32_t margin_type, float filter_threshold, float* loss_out,
+                          float* dX_out, float* dW_out, float* stats_out);
 int update_impl(pfc_ctx* ctx, float* W, float* v, const int32_t* idx, int64_t k,
                 const float* dW, float lr, float mu);
 

@@ -152,16 +152,31 @@ __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N
 // classes j, so the sums over j are in-lane; the bf16 tile is transposed through LDS so that E
 // is written in whole 512-byte rows.
 //
-// The element-wise part exists twice.  The plain version (5 VALU instructions per entry) serves
-// wavefronts whose part of the tile holds no label entry and no padding; only the few
-// wavefronts that do hold one take the guarded version.
+// The element-wise part exists in four versions.  GUARDED: the wavefront's part of the tile holds
+// a label entry or padding (few wavefronts do); the plain version costs 5 VALU instructions per
+// entry.  EXTRAS: the options are on -- negatives whose cosine exceeds `tau` are left out of the
+// softmax (the PFC* filter, Sec. 3.3 / Fig. 4 caption) and the largest non-label cosine of every
+// sample is tracked (for AMNCS, Sec. 3.3).
 // ---------------------------------------------------------------------------------------------
-template <class Cfg, bool GUARDED>
+struct LossParams {
+  float s, s_log2e;
+  float m, cos_m, sin_m;
+  int32_t cosface;   // 0: label logit s*cos(theta+m); 1: s*(cos(theta) - m)
+  float tau;         // filter threshold (entries with cosine > tau are dropped); >= 1: off
+  int32_t extras;    // filter and/or column maxima requested
+};
+
+__device__ __forceinline__ float label_logit(const LossParams& lp, float c) {
+  if (lp.cosface) return lp.s * (c - lp.m);
+  return lp.s * (c * lp.cos_m - sqrtf(fmaxf(1.f - c * c, 0.f)) * lp.sin_m);
+}
+
+template <class Cfg, bool GUARDED, bool EXTRAS>
 __device__ __forceinline__ void logits_epilogue_columns(
     const f32x16 (&acc)[Cfg::TM][Cfg::TN], int64_t j0, int i0, int B, int klim, int64_t kp,
-    const int (&ylane)[Cfg::TN], float s, float s_log2e, float cos_m, float sin_m, char* smem,
-    int SX, typename Cfg::elem* __restrict__ E, float* __restrict__ clabel,
-    float (&colsum)[Cfg::TN]) {
+    const int (&ylane)[Cfg::TN], const LossParams& lp, char* smem, int SX,
+    typename Cfg::elem* __restrict__ E, float* __restrict__ clabel, float (&colsum)[Cfg::TN],
+    float (&colmax)[Cfg::TN]) {
   using T = typename Cfg::elem;
   constexpr bool kStage = (sizeof(T) == 2);
 #pragma unroll
@@ -170,7 +185,7 @@ __device__ __forceinline__ void logits_epilogue_columns(
     const int i = i0 + il;
     const bool vi = i < B;
     const int yloc = ylane[bn];
-    float sum = 0.f, clab = 0.f;
+    float sum = 0.f, clab = 0.f, cmax = -2.f;
 #pragma unroll
     for (int bm = 0; bm < Cfg::TM; ++bm) {
 #pragma unroll
@@ -180,11 +195,19 @@ __device__ __forceinline__ void logits_epilogue_columns(
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float c = __builtin_amdgcn_fmed3f(acc[bm][bn][g4 * 4 + e], -1.f, 1.f);
-          float ev = __builtin_amdgcn_exp2f(c * s_log2e);   // exp(s*c); |s*c*log2(e)| <= 93
+          float ev = __builtin_amdgcn_exp2f(c * lp.s_log2e);   // exp(s*c); |s*c*log2(e)| <= 93
           if constexpr (GUARDED) {
             const bool lab = (jl + e == yloc);
-            ev = (vi && jl + e < klim && !lab) ? ev : 0.f;
+            const bool neg = vi && jl + e < klim && !lab;      // a real, non-label entry
+            ev = neg ? ev : 0.f;
             clab = lab ? c : clab;
+            if constexpr (EXTRAS) {
+              cmax = neg ? fmaxf(cmax, c) : cmax;
+              ev = (c > lp.tau) ? 0.f : ev;
+            }
+          } else if constexpr (EXTRAS) {
+            cmax = fmaxf(cmax, c);
+            ev = (c > lp.tau) ? 0.f : ev;
           }
           sum += ev;
           pack[e] = from_float<T>(ev);
@@ -203,21 +226,21 @@ __device__ __forceinline__ void logits_epilogue_columns(
     if constexpr (GUARDED) {
       if (yloc >= 0) {   // this lane holds sample i's label entry: it was left out of `sum`
         clabel[i] = clab;
-        const float zl = s * (clab * cos_m - sqrtf(fmaxf(1.f - clab * clab, 0.f)) * sin_m);
-        sum += __expf(zl);
+        sum += __expf(label_logit(lp, clab));
       }
     }
     sum += __shfl_xor(sum, 32, 64);
     colsum[bn] = sum;
+    if constexpr (EXTRAS) colmax[bn] = fmaxf(cmax, __shfl_xor(cmax, 32, 64));
   }
 }
 
-template <class Cfg>
+template <class Cfg, bool EXTRAS>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
     const typename Cfg::elem* __restrict__ Wn, const typename Cfg::elem* __restrict__ Xn, int D,
-    int64_t k, int B, int Bp, int64_t kp, const int32_t* __restrict__ yl, float s, float cos_m,
-    float sin_m, typename Cfg::elem* __restrict__ E, float* __restrict__ rowpart,
-    float* __restrict__ clabel, int tiles_j, int tiles_i) {
+    int64_t k, int B, int Bp, int64_t kp, const int32_t* __restrict__ yl, LossParams lp,
+    typename Cfg::elem* __restrict__ E, float* __restrict__ rowpart,
+    float* __restrict__ rowmaxpart, float* __restrict__ clabel, int tiles_j, int tiles_i) {
   using T = typename Cfg::elem;
   extern __shared__ __align__(16) char smem[];
   int tj, ti;
@@ -232,7 +255,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
   constexpr bool kStage = (sizeof(T) == 2);          // bf16: transpose the tile through LDS
   constexpr int SX = Cfg::BM * 2 + 8;                // staging row (one sample) stride in bytes
   constexpr int RED_OFF = Cfg::BN * SX;              // cross-wave reduction scratch behind it
-  static_assert(RED_OFF + Cfg::WM * Cfg::BN * 4 <= Cfg::LDS_BYTES, "epilogue LDS");
+  static_assert(RED_OFF + 2 * Cfg::WM * Cfg::BN * 4 <= Cfg::LDS_BYTES, "epilogue LDS");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t krem = k - j0;
   const int klim = krem < (int64_t)Cfg::BM ? (int)krem : Cfg::BM;   // valid classes in this tile
@@ -256,28 +279,36 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
   }
   const bool guarded = __any(any_label) || klim < Cfg::BM || i0 + Cfg::BN > B;   // wave-uniform
 
-  const float s_log2e = s * 1.44269504088896340736f;
-  float colsum[Cfg::TN];
+  float colsum[Cfg::TN], colmax[Cfg::TN];
+#pragma unroll
+  for (int bn = 0; bn < Cfg::TN; ++bn) colmax[bn] = -2.f;
   if (guarded)
-    logits_epilogue_columns<Cfg, true>(acc, j0, i0, B, klim, kp, ylane, s, s_log2e, cos_m, sin_m,
-                                       smem, SX, E, clabel, colsum);
+    logits_epilogue_columns<Cfg, true, EXTRAS>(acc, j0, i0, B, klim, kp, ylane, lp, smem, SX, E,
+                                               clabel, colsum, colmax);
   else
-    logits_epilogue_columns<Cfg, false>(acc, j0, i0, B, klim, kp, ylane, s, s_log2e, cos_m, sin_m,
-                                        smem, SX, E, clabel, colsum);
+    logits_epilogue_columns<Cfg, false, EXTRAS>(acc, j0, i0, B, klim, kp, ylane, lp, smem, SX, E,
+                                                clabel, colsum, colmax);
 
   // cross-wave reduction over the WM wavefronts that share a column (fixed order)
-  float* red = reinterpret_cast<float*>(smem + RED_OFF);   // [WM][BN]
+  float* red = reinterpret_cast<float*>(smem + RED_OFF);   // [WM][BN] sums, then [WM][BN] maxima
   if (lane < 32) {
 #pragma unroll
-    for (int bn = 0; bn < Cfg::TN; ++bn)
-      red[(wave / Cfg::WN) * Cfg::BN + (wave % Cfg::WN) * Cfg::WTN + bn * 32 + lane] = colsum[bn];
+    for (int bn = 0; bn < Cfg::TN; ++bn) {
+      const int o = (wave / Cfg::WN) * Cfg::BN + (wave % Cfg::WN) * Cfg::WTN + bn * 32 + lane;
+      red[o] = colsum[bn];
+      red[Cfg::WM * Cfg::BN + o] = colmax[bn];
+    }
   }
   __syncthreads();
   for (int t = threadIdx.x; t < Cfg::BN; t += Cfg::THREADS) {
-    float v = 0.f;
+    float v = 0.f, mx = -2.f;
 #pragma unroll
-    for (int w = 0; w < Cfg::WM; ++w) v += red[w * Cfg::BN + t];
+    for (int w = 0; w < Cfg::WM; ++w) {
+      v += red[w * Cfg::BN + t];
+      mx = fmaxf(mx, red[Cfg::WM * Cfg::BN + w * Cfg::BN + t]);
+    }
     rowpart[(int64_t)(i0 + t) * tiles_j + tj] = v;
+    if constexpr (EXTRAS) rowmaxpart[(int64_t)(i0 + t) * tiles_j + tj] = mx;
   }
   if constexpr (kStage) {
     // one wavefront instruction stores one whole row of the tile: BM * 2 bytes, 8 per lane
@@ -298,9 +329,10 @@ template <typename T, int NC>
 __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_j, int B, int Bp,
                                    int D, const float* __restrict__ X,
                                    const float* __restrict__ rnormX,
-                                   const float* __restrict__ clabel, float s, float cos_m,
-                                   float sin_m, float* __restrict__ rowscale,
-                                   float* __restrict__ dlabel, float* __restrict__ lossrow,
+                                   const float* __restrict__ clabel, LossParams lp,
+                                   const float* __restrict__ rowmaxpart,
+                                   float* __restrict__ rowscale, float* __restrict__ dlabel,
+                                   float* __restrict__ lossrow, float* __restrict__ rowmax,
                                    T* __restrict__ Xs) {
   const int lane = threadIdx.x & 63;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -310,21 +342,30 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
     float l = 0.f;
     for (int t = lane; t < tiles_j; t += 64) l += rowpart[(int64_t)i * tiles_j + t];
     l = wave_sum(l);
-    scale = s / ((float)B * l);
+    scale = lp.s / ((float)B * l);
+    float mx = -2.f;
+    if (lp.extras) {
+      for (int t = lane; t < tiles_j; t += 64) mx = fmaxf(mx, rowmaxpart[(int64_t)i * tiles_j + t]);
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    }
     if (lane == 0) {
       const float c = clabel[i];
       const float sin2 = 1.f - c * c;
-      const float zlab = s * (c * cos_m - sqrtf(fmaxf(sin2, 0.f)) * sin_m);
+      const float zlab = label_logit(lp, c);
       const float p = __expf(zlab) / l;
-      const float rho = cos_m + c * sin_m / sqrtf(fmaxf(sin2, kEpsSin2));
+      // d(label logit)/d cos / s: sin(theta+m)/sin(theta) for the angular margin, 1 for the cosine one
+      const float rho = lp.cosface ? 1.f : lp.cos_m + c * lp.sin_m / sqrtf(fmaxf(sin2, kEpsSin2));
       lossrow[i] = logf(l) - zlab;
       rowscale[i] = scale;
-      dlabel[i] = (s / (float)B) * (p - 1.f) * rho;
+      dlabel[i] = (lp.s / (float)B) * (p - 1.f) * rho;
+      rowmax[i] = mx;
     }
   } else if (lane == 0) {
     lossrow[i] = 0.f;
     rowscale[i] = 0.f;
     dlabel[i] = 0.f;
+    rowmax[i] = 0.f;
   }
   const float f = (i < B) ? rnormX[i] * scale : 0.f;
 #pragma unroll
@@ -500,20 +541,29 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
                                        const float* __restrict__ rowscale,
                                        const float* __restrict__ dlabel, float* __restrict__ dX,
                                        const float* __restrict__ lossrow,
-                                       float* __restrict__ loss_out) {
+                                       float* __restrict__ loss_out,
+                                       const float* __restrict__ clabel,
+                                       const float* __restrict__ rowmax,
+                                       float* __restrict__ stats_out) {
   const int lane = threadIdx.x & 63;
   if (blockIdx.x == gridDim.x - 1) {
-    // the extra last block: mean loss, summed in a fixed order (strided partials, then a tree)
+    // the extra last block: mean loss (and, on request, mean label cosine = APCS and mean largest
+    // non-label cosine = AMNCS), each summed in a fixed order (strided partials, then a tree)
     __shared__ float sm[256];
-    float v = 0.f;
-    for (int r = threadIdx.x; r < B; r += 256) v += lossrow[r];
-    sm[threadIdx.x] = v;
-    __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-      if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+    const int nq = stats_out ? 3 : 1;
+    for (int q = 0; q < nq; ++q) {
+      const float* src = q == 0 ? lossrow : q == 1 ? clabel : rowmax;
+      float v = 0.f;
+      for (int r = threadIdx.x; r < B; r += 256) v += src[r];
+      sm[threadIdx.x] = v;
+      __syncthreads();
+      for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+        __syncthreads();
+      }
+      if (threadIdx.x == 0) (q == 0 ? loss_out : stats_out + (q - 1))[0] = sm[0] / (float)B;
       __syncthreads();
     }
-    if (threadIdx.x == 0) loss_out[0] = sm[0] / (float)B;
     return;
   }
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -567,15 +617,14 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
 // ---------------------------------------------------------------------------------------------
 template <typename T, int NC>
 int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t k,
-        const int32_t* yl, int32_t B, float s, float m, float* loss_out, float* dX_out,
-        float* dW_out) {
+        const int32_t* yl, int32_t B, const LossParams& lp, float* loss_out, float* dX_out,
+        float* dW_out, float* stats_out) {
   using CfgF = TileCfg<T, 256, 256, 2, 4, false, false, 1>;   // logits: 256 classes x 256 samples
   using CfgW = TileCfg<T, 256, 256, 2, 4, true, true, 1>;   // dweight: 256 classes x 256 of D
   using CfgX = TileCfg<T, 256, 256, 2, 4, false, true, 2>;   // dfeatures: 256 samples x 256 of D
   const int D = c->D;
   const int Bp = (int)round_up(B, kPadB);
   const int64_t kp = round_up(k, kPadK);
-  const float cos_m = cosf(m), sin_m = sinf(m);
   T* Xn = (T*)c->Xn; T* Xs = (T*)c->Xs; T* Wn = (T*)c->Wn; T* E = (T*)c->E;
 
   auto norm_kernel = normalize_x_kernel<T, NC>;
@@ -588,7 +637,9 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
 
   static bool attr_done = false;   // per instantiation: raise the dynamic LDS limit once
   if (!attr_done) {
-    PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgF>,
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgF, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgF, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
@@ -598,13 +649,15 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   }
   {
     const int tiles_j = (int)(kp / CfgF::BM), tiles_i = Bp / CfgF::BN;
-    PFC_LAUNCH(c, KID_GEMM_LOGITS, gemm_logits_kernel<CfgF>, dim3(xcd_grid(tiles_i, tiles_j)),
-               dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, Bp, kp, yl, s, cos_m, sin_m,
-               E, c->rowpart, c->clabel, tiles_j, tiles_i);
+    // the options (filter, column maxima) have a kernel of their own: the plain one stays lean
+    auto logits_kernel = lp.extras ? gemm_logits_kernel<CfgF, true> : gemm_logits_kernel<CfgF, false>;
+    PFC_LAUNCH(c, KID_GEMM_LOGITS, logits_kernel, dim3(xcd_grid(tiles_i, tiles_j)),
+               dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, Bp, kp, yl, lp, E, c->rowpart,
+               c->rowmaxpart, c->clabel, tiles_j, tiles_i);
     auto combine_kernel = row_combine_kernel<T, NC>;
     PFC_LAUNCH(c, KID_ROW_COMBINE, combine_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowpart,
-               tiles_j, B, Bp, D, X, c->rnormX, c->clabel, s, cos_m, sin_m, c->rowscale, c->dlabel,
-               c->lossrow, Xs);
+               tiles_j, B, Bp, D, X, c->rnormX, c->clabel, lp, c->rowmaxpart, c->rowscale,
+               c->dlabel, c->lossrow, c->rowmax, Xs);
   }
   {
     const int tiles_j = (int)(kp / CfgW::BM), tiles_d = D / CfgW::BN;
@@ -630,7 +683,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   }
   PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3((B + 3) / 4 + 1), dim3(256), 0,
              c->dXpart, splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW,
-             c->rowscale, c->dlabel, dX_out, c->lossrow, loss_out);
+             c->rowscale, c->dlabel, dX_out, c->lossrow, loss_out, c->clabel, c->rowmax, stats_out);
   return PFC_OK;
 }
 
@@ -638,8 +691,19 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
 
 int forward_backward_impl(pfc_ctx* c, const float* X, const float* W, const int32_t* idx,
                           int64_t k, const int32_t* yl, int32_t B, float s, float m,
-                          float* loss_out, float* dX_out, float* dW_out) {
-#define PFC_RUN(T, NC) return run<T, NC>(c, X, W, idx, k, yl, B, s, m, loss_out, dX_out, dW_out)
+                          int32_t margin_type, float filter_threshold, float* loss_out,
+                          float* dX_out, float* dW_out, float* stats_out) {
+  LossParams lp;
+  lp.s = s;
+  lp.s_log2e = s * 1.44269504088896340736f;
+  lp.m = m;
+  lp.cos_m = cosf(m);
+  lp.sin_m = sinf(m);
+  lp.cosface = margin_type == PFC_MARGIN_COSFACE ? 1 : 0;
+  lp.tau = filter_threshold;
+  lp.extras = (filter_threshold < 1.f || stats_out != nullptr) ? 1 : 0;
+#define PFC_RUN(T, NC) \
+  return run<T, NC>(c, X, W, idx, k, yl, B, lp, loss_out, dX_out, dW_out, stats_out)
   const int nc = c->D / 256;
   if (c->precision == PFC_PRECISION_BF16) {
     switch (nc) {
