@@ -19,7 +19,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "sample_init",   "sample_mark",  "sample_hist0", "sample_scan0", "sample_hist1",
     "sample_scan1",  "sample_hist2", "sample_scan2", "sample_count", "sample_blkscan",
     "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_logits",
-    "row_combine",   "gemm_dweight", "dweight_label",
+    "row_combine",   "gemm_dweight", "dweight_reduce", "dweight_label",
     "gemm_dfeatures", "dfeatures_final", "update"};
 
 static int64_t ceil_rN(int64_t N, double r) { return (int64_t)ceil(r * (double)N); }
@@ -66,7 +66,7 @@ int pfc_destroy(pfc_ctx* c) {
   if (!c) return PFC_EINVAL;
   (void)hipStreamSynchronize(c->stream);
   void* bufs[] = {c->pos_bits, c->hist, c->sel, c->blk_cnt, c->blk_off, c->err_flag, c->Xn,
-                  c->Xs, c->rnormX, c->Wn, c->rnormW, c->E, c->rowpart, c->rowmaxpart, c->rowmax,
+                  c->Xs, c->rnormX, c->Wn, c->rnormW, c->head, c->E, c->rowpart, c->rowmaxpart, c->rowmax,
                   c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
@@ -98,6 +98,14 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   c->r_max = r_max;
   c->precision = precision;
   c->stream = (hipStream_t)hip_stream;
+  {
+    int dev = 0, ncu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        ncu < 1)
+      ncu = 256;
+    c->num_cu = ncu;
+  }
   c->k_cap = pfc_num_sampled(N, B_max, r_max);
   c->kp_cap = round_up(c->k_cap, kPadK);
   c->Bp_cap = (int32_t)round_up(B_max, kPadB);
@@ -120,6 +128,7 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(rnormX, Bp * 4);
   ALLOC(Wn, kp * Dz * es);
   ALLOC(rnormW, kp * 4);
+  ALLOC(head, kp * 4);
   ALLOC(E, Bp * kp * es);
   ALLOC(rowpart, (kp / kPadK) * 2 * Bp * 4);
   ALLOC(rowmaxpart, (kp / kPadK) * 2 * Bp * 4);

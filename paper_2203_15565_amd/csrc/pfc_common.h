@@ -37,6 +37,7 @@ enum KernelId {
   KID_GEMM_LOGITS,
   KID_ROW_COMBINE,
   KID_GEMM_DW,
+  KID_DW_REDUCE,
   KID_DW_LABEL,
   KID_GEMM_DX,
   KID_DX_FINAL,
@@ -86,6 +87,7 @@ struct pfc_ctx {
   float* rnormX;   // [Bp]
   void* Wn;        // [kp x D]   normalised sampled centers
   float* rnormW;   // [kp]
+  int32_t* head;   // [kp] first sample of the batch that carries class idx[j], else INT_MAX
   void* E;         // [Bp x kp]  exp(z), label column zeroed
   float* rowpart;  // [Bp x tiles_j] partial row sums of exp(z)
   float* rowmaxpart;  // [Bp x tiles_j] partial row maxima of the non-label cosines (options)
@@ -97,6 +99,7 @@ struct pfc_ctx {
   float* dXpart;   // [splits x Bp x D]
 
   // timing
+  int32_t num_cu;   // compute units of the device
   int32_t timing;
   hipEvent_t ev0[pfc::KID_COUNT];
   hipEvent_t ev1[pfc::KID_COUNT];

@@ -84,6 +84,7 @@ template <typename T, int NC>
 __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N,
                                           const int32_t* __restrict__ idx, int64_t k, int64_t kp,
                                           int D, T* __restrict__ Wn, float* __restrict__ rnormW,
+                                          int32_t* __restrict__ head,
                                           int32_t* __restrict__ err_flag) {
   constexpr int NB = 4;
   const int lane = threadIdx.x & 63;
@@ -119,7 +120,10 @@ __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N
     }
     ss = wave_sum(ss);
     const float rn = ok[u] ? 1.f / fmaxf(sqrtf(ss), kEpsNorm) : 0.f;
-    if (lane == 0) rnormW[j] = rn;
+    if (lane == 0) {
+      rnormW[j] = rn;
+      head[j] = 0x7fffffff;   // first sample carrying this class: filled in by row_combine
+    }
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       T o[4];
@@ -333,7 +337,8 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
                                    const float* __restrict__ rowmaxpart,
                                    float* __restrict__ rowscale, float* __restrict__ dlabel,
                                    float* __restrict__ lossrow, float* __restrict__ rowmax,
-                                   T* __restrict__ Xs) {
+                                   const int32_t* __restrict__ yl, int64_t k,
+                                   int32_t* __restrict__ head, T* __restrict__ Xs) {
   const int lane = threadIdx.x & 63;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (i >= Bp) return;
@@ -360,6 +365,8 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
       rowscale[i] = scale;
       dlabel[i] = (lp.s / (float)B) * (p - 1.f) * rho;
       rowmax[i] = mx;
+      const int32_t y = yl[i];
+      if (y >= 0 && (int64_t)y < k) atomicMin(&head[y], i);   // integer: order-independent
     }
   } else if (lane == 0) {
     lossrow[i] = 0.f;
@@ -389,52 +396,80 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
 
 // ---------------------------------------------------------------------------------------------
 // gemm_dweight: dWn[j][d] = sum_i E[i][j] * Xs[i][d] (both operands k-major); rows j < k are
-// written.
+// written.  When k is small and the batch large (the regime without extra negatives, Sec. 3.3)
+// there are too few tiles to fill the GPU: SPLIT cuts the batch (the reduction) into slices that
+// write partial tiles, summed in fixed order by dweight_reduce.
 // ---------------------------------------------------------------------------------------------
-template <class Cfg>
+template <class Cfg, bool SPLIT>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_kernel(
     const typename Cfg::elem* __restrict__ E, const typename Cfg::elem* __restrict__ Xs, int D,
-    int64_t k, int64_t kp, int Bp, float* __restrict__ dW, int tiles_j, int tiles_d) {
+    int64_t k, int64_t kp, int Bp, float* __restrict__ out, int tiles_j, int tiles_d,
+    int slabs_per, int splits) {
   extern __shared__ __align__(16) char smem[];
-  int tj, td;
-  if (!xcd_tile(blockIdx.x, tiles_d, tiles_j, tj, td)) return;
+  int tj, td, sp = 0, ns = Bp / Cfg::BK;
+  if constexpr (SPLIT) {
+    int tile;
+    if (!xcd_tile(blockIdx.x, tiles_j * tiles_d, splits, sp, tile)) return;
+    tj = tile / tiles_d;
+    td = tile % tiles_d;
+    ns -= sp * slabs_per;
+    if (ns > slabs_per) ns = slabs_per;
+  } else {
+    if (!xcd_tile(blockIdx.x, tiles_d, tiles_j, tj, td)) return;
+  }
   const int64_t j0 = (int64_t)tj * Cfg::BM;
   const int d0 = td * Cfg::BN;
+  const int64_t i0 = (int64_t)sp * slabs_per * Cfg::BK;   // first sample of this slice
   f32x16 acc[Cfg::TM][Cfg::TN];
   zero_acc<Cfg>(acc);
-  gemm_tile<Cfg>(E + j0, kp, Xs + d0, D, Bp / Cfg::BK, smem, acc);
+  gemm_tile<Cfg>(E + i0 * kp + j0, kp, Xs + i0 * D + d0, D, ns, smem, acc);
+  float* dst = SPLIT ? out + (int64_t)sp * kp * D : out;
 #pragma unroll
   for (int bm = 0; bm < Cfg::TM; ++bm)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int64_t j = j0 + acc_row<Cfg>(bm, r);
-      if (j < k) {
+      if (SPLIT || j < k) {
 #pragma unroll
         for (int bn = 0; bn < Cfg::TN; ++bn)
-          dW[j * D + d0 + acc_col<Cfg>(bn)] = acc[bm][bn][r];
+          dst[j * D + d0 + acc_col<Cfg>(bn)] = acc[bm][bn][r];
       }
     }
 }
 
+// dW[j][d] = sum over slices of part[slice][j][d], in slice order.
+__global__ void dweight_reduce_kernel(const float* __restrict__ part, int splits, int64_t k,
+                                      int64_t kp, int D, float* __restrict__ dW) {
+  const int64_t e4 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e4 >= k * D / 4) return;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int sp = 0; sp < splits; ++sp) {
+    const float4 t = *reinterpret_cast<const float4*>(part + (int64_t)sp * kp * D + e4 * 4);
+    a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+  }
+  *reinterpret_cast<float4*>(dW + e4 * 4) = a;
+}
+
 // dweight_label: dWn[y] += sum over samples i with label y of dlabel_i * xn_i.
-// Block i does the whole sum for its class if i is the first sample carrying that label.  The
+// Block i does the whole sum for its class if i is the first sample carrying that label
+// (head[y] == i, found with an integer atomicMin by row_combine).  The
 // matching samples are listed in ascending order; thread group g (one float4 column per thread)
 // sums the matches whose ordinal is congruent to g, and the groups are combined in fixed order,
 // so the result does not depend on timing.
 constexpr int kLabelThreads = 1024;
 __global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
     const float* __restrict__ X, int B, int D, const int32_t* __restrict__ yl, int64_t k,
-    const float* __restrict__ rnormX, const float* __restrict__ dlabel, float* __restrict__ dW) {
+    const int32_t* __restrict__ head, const float* __restrict__ rnormX,
+    const float* __restrict__ dlabel, float* __restrict__ dW) {
   __shared__ int s_list[kLabelThreads];
+  __shared__ float s_coef[kLabelThreads];   // dlabel_p / |x_p| of the listed samples
   __shared__ int s_wcnt[kLabelThreads / 64];
   __shared__ float4 s_part[kLabelThreads];
   const int i = blockIdx.x, t = threadIdx.x;
   const int lane = t & 63, wave = t >> 6;
   const int32_t y = yl[i];
   if (y < 0 || (int64_t)y >= k) return;
-  int seen = 0;
-  for (int p = t; p < i; p += kLabelThreads) seen |= (yl[p] == y);
-  if (__syncthreads_or(seen)) return;
+  if (head[y] != i) return;   // an earlier sample carries this label and does the sum
   const int cols = D >> 2;                 // float4 columns: 64 .. 256
   const int G = kLabelThreads / cols;      // thread groups
   const int col = t % cols, g = t / cols;
@@ -453,27 +488,33 @@ __global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
       if (w < wave) base += c;
       total += c;
     }
-    if (hit) s_list[base + before] = p;
+    if (hit) {
+      s_list[base + before] = p;
+      s_coef[base + before] = dlabel[p] * rnormX[p];
+    }
     __syncthreads();
-    // group g takes list entries whose global ordinal is congruent to g modulo G
+    // group g takes list entries whose global ordinal is congruent to g modulo G; eight row
+    // loads are in flight at a time, the additions stay in list order
     int e = (g - ordinal0 % G + G) % G;
-    for (; e + 3 * G < total; e += 4 * G) {
-      const int q0 = s_list[e], q1 = s_list[e + G], q2 = s_list[e + 2 * G], q3 = s_list[e + 3 * G];
-      const float4 x0 = *reinterpret_cast<const float4*>(X + (int64_t)q0 * D + col * 4);
-      const float4 x1 = *reinterpret_cast<const float4*>(X + (int64_t)q1 * D + col * 4);
-      const float4 x2 = *reinterpret_cast<const float4*>(X + (int64_t)q2 * D + col * 4);
-      const float4 x3 = *reinterpret_cast<const float4*>(X + (int64_t)q3 * D + col * 4);
-      const float a0 = dlabel[q0] * rnormX[q0], a1 = dlabel[q1] * rnormX[q1];
-      const float a2 = dlabel[q2] * rnormX[q2], a3 = dlabel[q3] * rnormX[q3];
-      acc.x += a0 * x0.x; acc.y += a0 * x0.y; acc.z += a0 * x0.z; acc.w += a0 * x0.w;
-      acc.x += a1 * x1.x; acc.y += a1 * x1.y; acc.z += a1 * x1.z; acc.w += a1 * x1.w;
-      acc.x += a2 * x2.x; acc.y += a2 * x2.y; acc.z += a2 * x2.z; acc.w += a2 * x2.w;
-      acc.x += a3 * x3.x; acc.y += a3 * x3.y; acc.z += a3 * x3.z; acc.w += a3 * x3.w;
+    constexpr int UN = 8;
+    for (; e + (UN - 1) * G < total; e += UN * G) {
+      float4 x[UN];
+      float a[UN];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const int q = s_list[e + u * G];
+        a[u] = s_coef[e + u * G];
+        x[u] = *reinterpret_cast<const float4*>(X + (int64_t)q * D + col * 4);
+      }
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        acc.x += a[u] * x[u].x; acc.y += a[u] * x[u].y; acc.z += a[u] * x[u].z; acc.w += a[u] * x[u].w;
+      }
     }
     for (; e < total; e += G) {
       const int q = s_list[e];
       const float4 x = *reinterpret_cast<const float4*>(X + (int64_t)q * D + col * 4);
-      const float a = dlabel[q] * rnormX[q];
+      const float a = s_coef[e];
       acc.x += a * x.x; acc.y += a * x.y; acc.z += a * x.z; acc.w += a * x.w;
     }
     ordinal0 += total;
@@ -633,7 +674,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
 
   auto gather_kernel = gather_normalize_w_kernel<T, NC>;
   PFC_LAUNCH(c, KID_GATHER_W, gather_kernel, dim3((unsigned)((kp / 4 + 3) / 4)), dim3(256), 0, W,
-             c->N, idx, k, kp, D, Wn, c->rnormW, c->err_flag);
+             c->N, idx, k, kp, D, Wn, c->rnormW, c->head, c->err_flag);
 
   static bool attr_done = false;   // per instantiation: raise the dynamic LDS limit once
   if (!attr_done) {
@@ -641,7 +682,9 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgF, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
-    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW>,
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_dfeatures_kernel<CfgX>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgX::LDS_BYTES));
@@ -657,16 +700,35 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     auto combine_kernel = row_combine_kernel<T, NC>;
     PFC_LAUNCH(c, KID_ROW_COMBINE, combine_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowpart,
                tiles_j, B, Bp, D, X, c->rnormX, c->clabel, lp, c->rowmaxpart, c->rowscale,
-               c->dlabel, c->lossrow, c->rowmax, Xs);
+               c->dlabel, c->lossrow, c->rowmax, yl, k, c->head, Xs);
   }
   {
     const int tiles_j = (int)(kp / CfgW::BM), tiles_d = D / CfgW::BN;
-    PFC_LAUNCH(c, KID_GEMM_DW, gemm_dweight_kernel<CfgW>, dim3(xcd_grid(tiles_d, tiles_j)),
-               dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs, D, k, kp, Bp, dW_out, tiles_j,
-               tiles_d);
+    const int slabs_total = Bp / CfgW::BK;
+    // slices of the batch when the tiles alone leave most CUs idle; the partial tiles borrow the
+    // dfeatures split buffer, which is not in use yet
+    int want = c->num_cu / (tiles_j * tiles_d);
+    const int64_t room = (int64_t)kMaxSplits * Bp / kp;
+    if (want > room) want = (int)room;
+    if (want > slabs_total / 8) want = slabs_total / 8;   // a slice must stay long enough to pay
+                                                          // for its own partial tile
+    if (want >= 2) {
+      const int slabs_per = (slabs_total + want - 1) / want;
+      const int nsp = (slabs_total + slabs_per - 1) / slabs_per;
+      PFC_LAUNCH(c, KID_GEMM_DW, (gemm_dweight_kernel<CfgW, true>),
+                 dim3(xcd_grid(tiles_j * tiles_d, nsp)), dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs,
+                 D, k, kp, Bp, c->dXpart, tiles_j, tiles_d, slabs_per, nsp);
+      PFC_LAUNCH(c, KID_DW_REDUCE, dweight_reduce_kernel,
+                 dim3((unsigned)((k * D / 4 + 255) / 256)), dim3(256), 0, c->dXpart, nsp, k, kp, D,
+                 dW_out);
+    } else {
+      PFC_LAUNCH(c, KID_GEMM_DW, (gemm_dweight_kernel<CfgW, false>),
+                 dim3(xcd_grid(tiles_d, tiles_j)), dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs, D, k,
+                 kp, Bp, dW_out, tiles_j, tiles_d, slabs_total, 1);
+    }
   }
   PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel, dim3(B), dim3(kLabelThreads), 0, X, B, D, yl,
-             k, c->rnormX, c->dlabel, dW_out);
+             k, c->head, c->rnormX, c->dlabel, dW_out);
   int splits;
   {
     const int tiles_i = Bp / CfgX::BM, tiles_d = D / CfgX::BN;

@@ -53,6 +53,12 @@ CONFIGS = {
                          steps=1, label_dist="zipf", zipf_alpha=1.2),
     "extreme": Workload("extreme", 5, B=2048, D=512, N=10_000_000, r=0.05, precision=1,
                         steps=1, label_dist="zipf", zipf_alpha=1.2),
+    # The paper's fastest setting (Sec. 3.3; Tab. 7 caption): no negative outside the batch is
+    # drawn (r below B/N, so k = number of distinct labels) and the batch is enlarged to 8K / 16K.
+    "ultrafast8k": Workload("ultrafast8k", 6, B=8192, D=512, N=2_059_906, r=1e-9, precision=1,
+                            steps=1, label_dist="zipf", zipf_alpha=1.2),
+    "ultrafast16k": Workload("ultrafast16k", 7, B=16384, D=512, N=2_059_906, r=1e-9, precision=1,
+                             steps=1, label_dist="zipf", zipf_alpha=1.2),
 }
 
 

@@ -220,7 +220,8 @@ def _device_weight(wl):
     return Wd
 
 
-@pytest.mark.parametrize("name,r", [("headline", 0.1), ("headline", 0.05), ("extreme", 0.05)])
+@pytest.mark.parametrize("name,r", [("headline", 0.1), ("headline", 0.05), ("extreme", 0.05),
+                                    ("ultrafast8k", 1e-9)])
 def test_full_size_step(name, r):
     """One whole step at the full class count, in the launch configuration bench.py times.
     The oracle runs on the sampled rows W[idx] only (the method never reads the others); rows
