@@ -315,11 +315,14 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
     if constexpr (EXTRAS) rowmaxpart[(int64_t)(i0 + t) * tiles_j + tj] = mx;
   }
   if constexpr (kStage) {
-    // one wavefront instruction stores one whole row of the tile: BM * 2 bytes, 8 per lane
-    static_assert(Cfg::BM == 256, "row write-out assumes 64 lanes x 4 classes");
-    for (int row = wave; row < Cfg::BN; row += Cfg::THREADS / 64) {
-      const uint2 v = *reinterpret_cast<const uint2*>(smem + row * SX + lane * 8);
-      *reinterpret_cast<uint2*>(E + (int64_t)(i0 + row) * kp + j0 + lane * 4) = v;
+    // whole rows of the tile (BM * 2 bytes, 8 per lane) leave in one piece
+    constexpr int LPR = Cfg::BM / 4;        // lanes per tile row
+    constexpr int RPW = 64 / LPR;           // tile rows per wavefront instruction
+    static_assert(LPR <= 64 && 64 % LPR == 0, "row write-out: 4 classes per lane");
+    const int sub = lane / LPR, l = lane % LPR;
+    for (int row = wave * RPW + sub; row < Cfg::BN; row += (Cfg::THREADS / 64) * RPW) {
+      const uint2 v = *reinterpret_cast<const uint2*>(smem + row * SX + l * 8);
+      *reinterpret_cast<uint2*>(E + (int64_t)(i0 + row) * kp + j0 + l * 4) = v;
     }
   }
 }
@@ -660,9 +663,9 @@ template <typename T, int NC>
 int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t k,
         const int32_t* yl, int32_t B, const LossParams& lp, float* loss_out, float* dX_out,
         float* dW_out, float* stats_out) {
-  using CfgF = TileCfg<T, 256, 256, 2, 4, false, false, 1>;   // logits: 256 classes x 256 samples
-  using CfgW = TileCfg<T, 256, 256, 2, 4, true, true, 1>;   // dweight: 256 classes x 256 of D
-  using CfgX = TileCfg<T, 256, 256, 2, 4, false, true, 2>;   // dfeatures: 256 samples x 256 of D
+  using CfgF = TileCfg<T, 256, 256, 2, 4, false, false>;   // logits: 256 classes x 256 samples
+  using CfgW = TileCfg<T, 256, 256, 2, 4, true, true>;     // dweight: 256 classes x 256 of D
+  using CfgX = TileCfg<T, 256, 256, 2, 4, false, true>;    // dfeatures: 256 samples x 256 of D
   const int D = c->D;
   const int Bp = (int)round_up(B, kPadB);
   const int64_t kp = round_up(k, kPadK);

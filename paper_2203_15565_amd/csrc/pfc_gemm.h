@@ -11,8 +11,9 @@
 // producers: the main loop has no bounds checks.
 //
 // A workgroup of WM x WN wavefronts (64 lanes each) owns a BM x BN tile of C.  K is walked in
-// slabs of BK = 64 (bf16) or 32 (fp32) reduction steps, double buffered in LDS; global loads of
-// slab s+1 are in flight in registers while slab s is multiplied.
+// slabs of BK = 64 (bf16) or 32 (fp32) reduction steps, double buffered in LDS; slab s+1 waits in
+// the second LDS stage and the global loads of slab s+2 are in flight in registers while slab s
+// is multiplied.
 //
 // LDS layouts of one operand slab (R = BM or BN rows of the operand tile):
 //   k contiguous: R rows of 128 bytes, row stride 144: a 16-byte fragment read by 16 consecutive
@@ -54,12 +55,11 @@ struct OperandLds {
   static constexpr int CHUNKS = ROWS * CHUNKS_PER_ROW;                           // 16-byte chunks
 };
 
-template <typename T, int BM_, int BN_, int WM_, int WN_, bool AKM, bool BKM, int DIST_ = 2>
+template <typename T, int BM_, int BN_, int WM_, int WN_, bool AKM, bool BKM>
 struct TileCfg {
   using elem = T;
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
   static constexpr bool A_KMAJOR = AKM, B_KMAJOR = BKM;
-  static constexpr int DIST = DIST_;   // global-load prefetch distance in slabs (1 or 2)
   static constexpr int BK = kSlabBytes / (int)sizeof(T);   // reduction steps per slab
   static constexpr int THREADS = WM * WN * 64;
   static constexpr int WTM = BM / WM, WTN = BN / WN;       // tile of one wavefront
@@ -134,6 +134,11 @@ struct Stager {
       r[4 * p + 0] = t[0]; r[4 * p + 1] = t[1]; r[4 * p + 2] = t[2]; r[4 * p + 3] = t[3];
     }
     return r;
+  }
+  // chunk p of slab s alone (lets the caller spread the loads of a slab between its MFMAs)
+  __device__ __forceinline__ void load_chunk(int s, int p, Regs& r) const {
+    const u32x4 t = *reinterpret_cast<const u32x4*>(base + (int64_t)s * slab + p * pass + toff);
+    r[4 * p + 0] = t[0]; r[4 * p + 1] = t[1]; r[4 * p + 2] = t[2]; r[4 * p + 3] = t[3];
   }
   __device__ __forceinline__ void store(char* region, const Regs& r) const {
 #pragma unroll
@@ -211,34 +216,22 @@ __device__ __forceinline__ void mma_group(const Frags<Cfg>& f, f32x16 (&acc)[Cfg
 
 constexpr int kGroups = kSlabBytes / 32;   // reduction groups (fragment reads) per slab
 
-// Groups 0 .. kGroups-2 of the slab in `stage`: the fragments of group g+1 are read while the
-// MFMAs of group g run.  On entry fc holds group 0; on exit it holds the last group, not yet
-// multiplied.
-template <class Cfg>
-__device__ __forceinline__ void mma_slab_head(const char* stage, int wm, int wn, Frags<Cfg>& fc,
-                                              f32x16 (&acc)[Cfg::TM][Cfg::TN]) {
-#pragma unroll
-  for (int g = 0; g + 1 < kGroups; ++g) {
-    Frags<Cfg> fn;
-    read_group<Cfg>(stage, g + 1, wm, wn, fn);
-    __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs they do not feed
-    mma_group<Cfg>(fc, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    fc = fn;
-  }
-}
-
 // Accumulate acc += A_tile * B_tile^T over `nslabs` slabs of K.
 //   A: element (first of this workgroup's BM tile rows, first reduction step of its range)
 //   B: likewise for its BN tile rows;  lda / ldb in elements.
 //   smem: Cfg::LDS_BYTES bytes, 16-byte aligned.  Ends with a barrier (smem may be reused).
-// Software pipeline, three levels deep:
-//   * two LDS stages and two register sets: while slab s is multiplied out of LDS, slab s+1 sits
-//     in one register set (stored to the other stage at the end of the iteration) and slab s+2 is
-//     in flight into the other set, so a global load has two iterations to arrive;
+// Software pipeline (two LDS stages, one register set, global loads two slabs ahead):
+//   * at the top of iteration s the registers hold slab s+1, loaded during iteration s-1, so it
+//     has had a whole iteration to arrive; it goes to the idle LDS stage at once, and the barrier
+//     at the end of the iteration publishes it;
+//   * the loads of slab s+2 then refill the registers, issued one at a time between the MFMAs of
+//     the first two groups: a wavefront that issues a whole slab in one burst queues up at the
+//     memory pipe (measured: up to 1400 cycles) with its MFMAs stuck behind the loads;
 //   * inside a slab the fragments of group g+1 are read from LDS while group g is multiplied;
 //   * the last group of a slab is multiplied AFTER the barrier, behind the first fragment reads
 //     of the next slab, so the LDS latency at the slab boundary is covered as well.
+// Slab numbers past the end are clamped to the last slab: such loads and LDS stores are
+// redundant but in bounds, and keep the loop body free of branches.
 template <class Cfg>
 __device__ __forceinline__ void gemm_tile(const typename Cfg::elem* __restrict__ A, int64_t lda,
                                           const typename Cfg::elem* __restrict__ B, int64_t ldb,
@@ -259,86 +252,56 @@ __device__ __forceinline__ void gemm_tile(const typename Cfg::elem* __restrict__
   char* st0 = smem;
   char* st1 = smem + Cfg::STAGE_BYTES;
   const int last = nslabs - 1;
+  constexpr int NA = Cfg::A_CHUNKS, NL = Cfg::A_CHUNKS + Cfg::B_CHUNKS;
+  constexpr int MM = Cfg::TM * Cfg::TN;            // MFMAs per group
+  constexpr int PER = (NL + 1) / 2;                // loads placed in each of the first two groups
+  static_assert(PER <= (MM + 1) / 2, "one load in front of every other MFMA at most");
+
+  // prologue: slabs 0 and 1 are requested back to back; slab 0 goes to stage 0
+  typename SA::Regs a0 = {};
+  typename SB::Regs b0 = {};
+  {
+    typename SA::Regs af = sa.load(0);
+    typename SB::Regs bf = sb.load(0);
+    a0 = sa.load(last < 1 ? last : 1);
+    b0 = sb.load(last < 1 ? last : 1);
+    sa.store(st0, af);
+    sb.store(st0 + Cfg::A_BYTES, bf);
+  }
+  __syncthreads();
   Frags<Cfg> fc;
-  if constexpr (Cfg::DIST == 2) {
-    typename SA::Regs a0 = {}, a1 = {};
-    typename SB::Regs b0 = {}, b1 = {};
-    a0 = sa.load(0);
-    b0 = sb.load(0);
-    a1 = sa.load(last < 1 ? last : 1);
-    b1 = sb.load(last < 1 ? last : 1);
-    sa.store(st0, a0);
-    sb.store(st0 + Cfg::A_BYTES, b0);
-    a0 = sa.load(last < 2 ? last : 2);
-    b0 = sb.load(last < 2 ? last : 2);
-    __syncthreads();
-    read_group<Cfg>(st0, 0, wm, wn, fc);
-    // Invariant at the top of iteration s (even): stage 0 holds slab s, set 1 holds slab s+1,
-    // set 0 holds slab s+2, fc holds group 0 of slab s.  Slab numbers past the end are clamped to
-    // the last slab: such loads, LDS stores and fragment reads are redundant but in bounds, and
-    // keep the loop body free of branches.
-    int s = 0;
-    for (; s + 1 < nslabs; s += 2) {
-      mma_slab_head<Cfg>(st0, wm, wn, fc, acc);
-      sa.store(st1, a1);
-      sb.store(st1 + Cfg::A_BYTES, b1);
-      a1 = sa.load(s + 3 < last ? s + 3 : last);
-      b1 = sb.load(s + 3 < last ? s + 3 : last);
-      __syncthreads();
-      {
-        Frags<Cfg> fn;
-        read_group<Cfg>(st1, 0, wm, wn, fn);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_group<Cfg>(fc, acc);
-        __builtin_amdgcn_sched_barrier(0);
-        fc = fn;
-      }
-      mma_slab_head<Cfg>(st1, wm, wn, fc, acc);
-      sa.store(st0, a0);
-      sb.store(st0 + Cfg::A_BYTES, b0);
-      a0 = sa.load(s + 4 < last ? s + 4 : last);
-      b0 = sb.load(s + 4 < last ? s + 4 : last);
-      __syncthreads();
-      {
-        Frags<Cfg> fn;
-        read_group<Cfg>(st0, 0, wm, wn, fn);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_group<Cfg>(fc, acc);
-        __builtin_amdgcn_sched_barrier(0);
-        fc = fn;
-      }
-    }
-    if (s < nslabs) {   // odd count: the last slab sits in stage 0 and fc holds its group 0
-      mma_slab_head<Cfg>(st0, wm, wn, fc, acc);
-      mma_group<Cfg>(fc, acc);
-    }
-  } else {
-    // One register set: the loads of slab s+1 are issued before slab s is multiplied and stored
-    // to the other stage behind it.
-    typename SA::Regs a0 = {};
-    typename SB::Regs b0 = {};
-    a0 = sa.load(0);
-    b0 = sb.load(0);
-    sa.store(st0, a0);
-    sb.store(st0 + Cfg::A_BYTES, b0);
-    __syncthreads();
-    read_group<Cfg>(st0, 0, wm, wn, fc);
-    for (int s = 0; s < nslabs; ++s) {
-      char* cur = (s & 1) ? st1 : st0;
-      char* nxt = (s & 1) ? st0 : st1;
-      a0 = sa.load(s + 1 < last ? s + 1 : last);
-      b0 = sb.load(s + 1 < last ? s + 1 : last);
-      mma_slab_head<Cfg>(cur, wm, wn, fc, acc);
-      sa.store(nxt, a0);
-      sb.store(nxt + Cfg::A_BYTES, b0);
-      __syncthreads();
+  read_group<Cfg>(st0, 0, wm, wn, fc);
+  for (int s = 0; s < nslabs; ++s) {
+    char* cur = (s & 1) ? st1 : st0;
+    char* nxt = (s & 1) ? st0 : st1;
+    const int s2 = s + 2 < last ? s + 2 : last;
+    sa.store(nxt, a0);
+    sb.store(nxt + Cfg::A_BYTES, b0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g + 1 < kGroups; ++g) {
       Frags<Cfg> fn;
-      read_group<Cfg>(nxt, 0, wm, wn, fn);
-      __builtin_amdgcn_sched_barrier(0);
-      mma_group<Cfg>(fc, acc);
+      read_group<Cfg>(cur, g + 1, wm, wn, fn);
+      __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs they do not feed
+#pragma unroll
+      for (int q = 0; q < MM; ++q) {
+        const int li = g * PER + q / 2;    // chunk to request in front of this MFMA
+        if (g < 2 && (q & 1) == 0 && q / 2 < PER && li < NL) {
+          if (li < NA) sa.load_chunk(s2, li, a0);
+          else sb.load_chunk(s2, li - NA, b0);
+        }
+        mfma_group<T>(fc.a[q / Cfg::TN], fc.b[q % Cfg::TN], acc[q / Cfg::TN][q % Cfg::TN]);
+      }
       __builtin_amdgcn_sched_barrier(0);
       fc = fn;
     }
+    __syncthreads();
+    Frags<Cfg> fn;
+    read_group<Cfg>(nxt, 0, wm, wn, fn);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_group<Cfg>(fc, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    fc = fn;
   }
   __syncthreads();
 }
