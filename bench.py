@@ -45,6 +45,9 @@ def algorithmic_work(B: int, D: int, k: int, precision: int) -> dict:
         "gemm_dfeatures": ("mfma", gemm),
         "gather_normalize_w": ("hbm", k * D * (4 + es) + 4.0 * k),
         "update": ("hbm", 5.0 * k * D * 4),
+        # the dweight GEMM that ends in the update of its rows: E and Xs in, W and v in and out;
+        # its 2*B*D*k flops need less time at the MFMA peak than these bytes at the HBM peak
+        "gemm_dweight_update": ("hbm", float(B) * k * es + float(B) * D * es + 4.0 * k * D * 4),
     }
 
 
@@ -56,6 +59,8 @@ def main() -> int:
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--r", type=float, default=None, help="override the sampling ratio")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="pfc_forward_backward + pfc_update instead of the one fused call")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -101,8 +106,12 @@ def main() -> int:
 
     def step(t: int) -> int:
         k = ctx.pfc_sample(labels[t], wl.r, wl.seed, t, idx, yl)
-        ctx.pfc_forward_backward(feats[t], Wd, idx, k, yl, wl.s, wl.m, loss, dX, dW)
-        ctx.pfc_update(Wd, vd, idx, k, dW, wl.lr, wl.mu)
+        if args.two_calls:
+            ctx.pfc_forward_backward(feats[t], Wd, idx, k, yl, wl.s, wl.m, loss, dX, dW)
+            ctx.pfc_update(Wd, vd, idx, k, dW, wl.lr, wl.mu)
+        else:   # same results; the center gradient stays inside the library
+            ctx.pfc_forward_backward_update(feats[t], Wd, vd, idx, k, yl, wl.s, wl.m, wl.lr, wl.mu,
+                                            loss, dX)
         return k
 
     # ---- cpu baseline: the oracle, one whole step on the same inputs (state before any step) --
@@ -211,7 +220,9 @@ def main() -> int:
         "config": {"workload": "%s: B=%d D=%d N=%d r=%g k=%d, Zipf(%.1f) labels, s=%g m=%g, "
                                "SGD lr=%g mu=%g" % (wl.name, wl.B, wl.D, wl.N, wl.r, k,
                                                     wl.zipf_alpha, wl.s, wl.m, wl.lr, wl.mu),
-                   "B": wl.B, "D": wl.D, "N": wl.N, "r": wl.r, "k": k},
+                   "B": wl.B, "D": wl.D, "N": wl.N, "r": wl.r, "k": k,
+                   "calls": "pfc_sample + pfc_forward_backward + pfc_update" if args.two_calls
+                   else "pfc_sample + pfc_forward_backward_update"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "measured_peaks": measured,

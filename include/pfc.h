@@ -144,6 +144,24 @@ int pfc_forward_backward_ex(pfc_ctx* ctx, const float* features, const float* we
 int pfc_update(pfc_ctx* ctx, float* weight, float* momentum, const int32_t* idx, int64_t k,
                const float* dweight, float lr, float mu);
 
+/*
+ * pfc_forward_backward_update -- pfc_forward_backward_ex followed by pfc_update in one call
+ * (Eq. 1-4 as above): loss and feature gradients come out, the sampled rows of weight and
+ * momentum are updated in place, and the center gradient is consumed where it is produced
+ * instead of crossing the boundary.  The results are those of the two calls in a row (the
+ * feature gradient and the loss are taken before any row changes).  With D = 512 the backward
+ * GEMM for the centers applies the update in its own epilogue and the k x D gradient never
+ * reaches memory; otherwise it passes through a buffer of the context.
+ *   weight, momentum  dev, fp32[N x D], updated in place on the rows in idx only
+ *   lr, mu            learning rate and momentum of pfc_update
+ *   the other arguments are those of pfc_forward_backward_ex (there is no dweight_out).
+ */
+int pfc_forward_backward_update(pfc_ctx* ctx, const float* features, float* weight,
+                                float* momentum, const int32_t* idx, int64_t k,
+                                const int32_t* labels_local, int32_t B, float s, float m,
+                                int32_t margin_type, float filter_threshold, float lr, float mu,
+                                float* loss_out, float* dfeatures_out, float* stats_out);
+
 /* Wait for the stream and report: PFC_ELABEL if any kernel since the last pfc_check saw an
  * out-of-range label or index (the flag is cleared), PFC_EHIP on a HIP error, else PFC_OK. */
 int pfc_check(pfc_ctx* ctx);

@@ -25,7 +25,7 @@ MARGIN_COSFACE = 1
 
 EXPORTS = [
     "pfc_create", "pfc_destroy", "pfc_num_sampled", "pfc_sample", "pfc_sample_masked",
-    "pfc_forward_backward", "pfc_forward_backward_ex", "pfc_update", "pfc_check", "pfc_set_timing", "pfc_get_timing",
+    "pfc_forward_backward", "pfc_forward_backward_ex", "pfc_forward_backward_update", "pfc_update", "pfc_check", "pfc_set_timing", "pfc_get_timing",
     "pfc_strerror", "pfc_last_hip_error", "pfc_probe_stream_copy", "pfc_probe_mfma_bf16",
 ]
 
@@ -70,6 +70,9 @@ def load() -> ctypes.CDLL:
     lib.pfc_forward_backward_ex.argtypes = [vp, vp, vp, vp, i64, vp, i32, f32, f32, i32, f32, vp, vp,
                                             vp, vp]
     lib.pfc_forward_backward_ex.restype = c.c_int
+    lib.pfc_forward_backward_update.argtypes = [vp, vp, vp, vp, vp, i64, vp, i32, f32, f32, i32, f32,
+                                                f32, f32, vp, vp, vp]
+    lib.pfc_forward_backward_update.restype = c.c_int
     lib.pfc_update.argtypes = [vp, vp, vp, vp, i64, vp, f32, f32]
     lib.pfc_update.restype = c.c_int
     lib.pfc_check.argtypes = [vp]
@@ -161,6 +164,18 @@ class Context:
                                             _ptr(stats_out))
         if rc != PFC_OK:
             raise PfcError(rc, "pfc_forward_backward_ex")
+
+    def pfc_forward_backward_update(self, features, weight, momentum, idx, k: int, labels_local,
+                                    s: float, m: float, lr: float, mu: float, loss_out,
+                                    dfeatures_out, margin_type: int = MARGIN_ARCFACE,
+                                    filter_threshold: float = 2.0, stats_out=None) -> None:
+        rc = load().pfc_forward_backward_update(self._h, _ptr(features), _ptr(weight),
+                                                _ptr(momentum), _ptr(idx), k, _ptr(labels_local),
+                                                features.shape[0], s, m, margin_type,
+                                                filter_threshold, lr, mu, _ptr(loss_out),
+                                                _ptr(dfeatures_out), _ptr(stats_out))
+        if rc != PFC_OK:
+            raise PfcError(rc, "pfc_forward_backward_update")
 
     def pfc_update(self, weight, momentum, idx, k: int, dweight, lr: float, mu: float) -> None:
         rc = load().pfc_update(self._h, _ptr(weight), _ptr(momentum), _ptr(idx), k, _ptr(dweight),

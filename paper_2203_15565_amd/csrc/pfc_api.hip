@@ -20,7 +20,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "sample_scan1",  "sample_hist2", "sample_scan2", "sample_count", "sample_blkscan",
     "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_logits",
     "row_combine",   "gemm_dweight", "dweight_reduce", "dweight_label",
-    "gemm_dfeatures", "dfeatures_final", "update"};
+    "gemm_dfeatures", "dfeatures_final", "update", "gemm_dweight_update"};
 
 static int64_t ceil_rN(int64_t N, double r) { return (int64_t)ceil(r * (double)N); }
 
@@ -67,7 +67,7 @@ int pfc_destroy(pfc_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   void* bufs[] = {c->pos_bits, c->hist, c->sel, c->blk_cnt, c->blk_off, c->err_flag, c->Xn,
                   c->Xs, c->rnormX, c->Wn, c->rnormW, c->head, c->E, c->rowpart, c->rowmaxpart, c->rowmax,
-                  c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart};
+                  c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart, c->dlab, c->dWtmp};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -138,6 +138,8 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(dlabel, Bp * 4);
   ALLOC(lossrow, Bp * 4);
   ALLOC(dXpart, (size_t)kMaxSplits * Bp * Dz * 4);
+  ALLOC(dlab, Bp * Dz * 4);
+  ALLOC(dWtmp, (size_t)c->k_cap * Dz * 4);
 #undef ALLOC
   if (rc == PFC_OK) {
     hipError_t e = hipHostMalloc((void**)&c->host_pin, 64, hipHostMallocDefault);
@@ -228,7 +230,25 @@ int pfc_forward_backward_ex(pfc_ctx* c, const float* X, const float* W, const in
   if (!(m >= 0.f) || !(m < 3.14159265f)) return PFC_EINVAL;
   if (!(filter_threshold == filter_threshold) || filter_threshold < -1.f) return PFC_EINVAL;
   return forward_backward_impl(c, X, W, idx, k, yl, B, s, m, margin_type, filter_threshold,
-                               loss_out, dX_out, dW_out, stats_out);
+                               loss_out, dX_out, dW_out, stats_out, nullptr);
+}
+
+int pfc_forward_backward_update(pfc_ctx* c, const float* X, float* W, float* v,
+                                const int32_t* idx, int64_t k, const int32_t* yl, int32_t B,
+                                float s, float m, int32_t margin_type, float filter_threshold,
+                                float lr, float mu, float* loss_out, float* dX_out,
+                                float* stats_out) {
+  if (!c || !X || !W || !v || !idx || !yl || !loss_out || !dX_out) return PFC_EINVAL;
+  if (B < 1 || B > c->B_max) return PFC_EINVAL;
+  if (k < 1 || k > c->k_cap || k > c->N) return PFC_EINVAL;
+  if (!(s > 0.f) || !(s <= 64.f)) return PFC_EINVAL;
+  if (margin_type != PFC_MARGIN_ARCFACE && margin_type != PFC_MARGIN_COSFACE) return PFC_EINVAL;
+  if (!(m >= 0.f) || !(m < 3.14159265f)) return PFC_EINVAL;
+  if (!(filter_threshold == filter_threshold) || filter_threshold < -1.f) return PFC_EINVAL;
+  if (!(lr == lr) || !(mu == mu)) return PFC_EINVAL;
+  UpdateArgs upd{W, v, lr, mu};
+  return forward_backward_impl(c, X, W, idx, k, yl, B, s, m, margin_type, filter_threshold,
+                               loss_out, dX_out, c->dWtmp, stats_out, &upd);
 }
 
 int pfc_forward_backward(pfc_ctx* c, const float* X, const float* W, const int32_t* idx,

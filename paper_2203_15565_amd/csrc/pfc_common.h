@@ -42,6 +42,7 @@ enum KernelId {
   KID_GEMM_DX,
   KID_DX_FINAL,
   KID_UPDATE,
+  KID_GEMM_DW_UPDATE,
   KID_COUNT
 };
 
@@ -97,6 +98,8 @@ struct pfc_ctx {
   float* dlabel;   // [Bp] (s/B)(p_iy - 1) rho_i
   float* lossrow;  // [Bp]
   float* dXpart;   // [splits x Bp x D]
+  float* dlab;     // [Bp x D] label-column part of dWn, one row per first sample of a class (fused step)
+  float* dWtmp;    // [k_cap x D] dWn of the fused step whenever its one-kernel form does not apply
 
   // timing
   int32_t num_cu;   // compute units of the device
@@ -141,6 +144,13 @@ struct TimedLaunch {
   } while (0);                                                                         \
   PFC_HIP(hipGetLastError())
 
+// Present when forward/backward is to end in the update of the sampled rows (the fused step).
+struct UpdateArgs {
+  float* W;   // [N x D] in/out
+  float* v;   // [N x D] in/out
+  float lr, mu;
+};
+
 // entry points implemented per translation unit (called by the extern "C" layer)
 int sample_impl(pfc_ctx* ctx, const int64_t* labels, int32_t B, double r, uint64_t seed,
                 uint64_t step, uint32_t score_mask, int32_t* idx_out, int32_t* yl_out,
@@ -148,7 +158,7 @@ int sample_impl(pfc_ctx* ctx, const int64_t* labels, int32_t B, double r, uint64
 int forward_backward_impl(pfc_ctx* ctx, const float* X, const float* W, const int32_t* idx,
                           int64_t k, const int32_t* yl, int32_t B, float s, float m,
                           int32_t margin_type, float filter_threshold, float* loss_out,
-                          float* dX_out, float* dW_out, float* stats_out);
+                          float* dX_out, float* dW_out, float* stats_out, const UpdateArgs* upd);
 int update_impl(pfc_ctx* ctx, float* W, float* v, const int32_t* idx, int64_t k,
                 const float* dW, float lr, float mu);
 

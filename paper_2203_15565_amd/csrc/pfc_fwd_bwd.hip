@@ -18,6 +18,7 @@
 // reference (zero) serves every tile, so p_ij = E_ij / l_i with l_i known only after the GEMM.
 // The label column is kept out of E (stored as zero) and handled in fp32 on the side, where
 // (p - 1) and the margin derivative are formed without bf16 rounding.
+#include <limits.h>
 #include <math.h>
 
 #include "pfc_common.h"
@@ -459,7 +460,10 @@ __global__ void dweight_reduce_kernel(const float* __restrict__ part, int splits
 // matching samples are listed in ascending order; thread group g (one float4 column per thread)
 // sums the matches whose ordinal is congruent to g, and the groups are combined in fixed order,
 // so the result does not depend on timing.
+// COMPACT (fused step): the sum is not added to dWn[y] but written to row i of a B x D side
+// buffer, i being that first sample; the fused GEMM picks it up through head[].
 constexpr int kLabelThreads = 1024;
+template <bool COMPACT>
 __global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
     const float* __restrict__ X, int B, int D, const int32_t* __restrict__ yl, int64_t k,
     const int32_t* __restrict__ head, const float* __restrict__ rnormX,
@@ -531,10 +535,146 @@ __global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
       const float4 o = s_part[gg * cols + col];
       r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w;
     }
-    float4* dst = reinterpret_cast<float4*>(dW + (int64_t)y * D + col * 4);
-    float4 cur = *dst;
-    cur.x += r.x; cur.y += r.y; cur.z += r.z; cur.w += r.w;
-    *dst = cur;
+    if constexpr (COMPACT) {
+      *reinterpret_cast<float4*>(dW + (int64_t)i * D + col * 4) = r;
+    } else {
+      float4* dst = reinterpret_cast<float4*>(dW + (int64_t)y * D + col * 4);
+      float4 cur = *dst;
+      cur.x += r.x; cur.y += r.y; cur.z += r.z; cur.w += r.w;
+      *dst = cur;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// gemm_dweight_update (fused step): the dweight GEMM on tiles that span all D columns, followed
+// in the same workgroup by the SGD-momentum update of the tile's rows (Eq. 3; text after Eq. 4),
+// so dWn is never written to memory: dWn_j = GEMM row + label part, g = (dWn - <dWn,wn> wn)/|w|,
+// v <- mu v + g, W <- W - lr v, with the arithmetic of update_kernel in the same order.
+// The accumulators go through LDS one half of the tile at a time (the rows of the wavefronts
+// with the same wm); then every wavefront takes whole rows, 16 bytes per lane and column chunk,
+// RB rows in flight.
+// ---------------------------------------------------------------------------------------------
+template <class Cfg>
+struct FusedUpdateLds {
+  static constexpr int HR = Cfg::WTM;               // rows per half
+  static constexpr int SROW = Cfg::BN + 4;          // floats per staged row (+4: the two rows a
+                                                    // store instruction touches fall 16 banks apart)
+  static constexpr int BYTES = HR * SROW * 4;
+  static constexpr int LDS = BYTES > Cfg::LDS_BYTES ? BYTES : Cfg::LDS_BYTES;
+};
+
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_update_kernel(
+    const typename Cfg::elem* __restrict__ E, const typename Cfg::elem* __restrict__ Xs, int64_t k,
+    int64_t kp, int Bp, const int32_t* __restrict__ idx, const int32_t* __restrict__ head,
+    const float* __restrict__ lab, float* __restrict__ W, float* __restrict__ V, int64_t N,
+    float lr, float mu, int32_t* __restrict__ err_flag) {
+  using FL = FusedUpdateLds<Cfg>;
+  constexpr int D = Cfg::BN, NC = D / 256, HR = FL::HR, SROW = FL::SROW;
+  constexpr int WAVES = Cfg::THREADS / 64, RPW = HR / WAVES;   // rows per wavefront and half
+  constexpr int ROWS = Cfg::WM * RPW;                           // rows per wavefront and tile
+  constexpr int WIN = 4;                                        // rows of W and v in flight
+  static_assert(D % 256 == 0 && HR % WAVES == 0 && ROWS <= 64 && WIN <= ROWS, "fused update geometry");
+  extern __shared__ __align__(16) char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t j0 = (int64_t)blockIdx.x * Cfg::BM;
+
+  // Row n of this wavefront (n = h*RPW + q) is tile row h*HR + q*WAVES + wave: neighbouring
+  // wavefronts take neighbouring rows.  Lane n fetches its class id and label head now, so that
+  // the epilogue starts its row loads without a dependent index load in front.
+  int32_t idxv = -1, headv = INT_MAX;
+  if (lane < ROWS) {
+    const int64_t j = j0 + (lane / RPW) * HR + (lane % RPW) * WAVES + wave;
+    if (j < k) {
+      idxv = idx[j];
+      headv = head[j];
+      if (idxv < 0 || (int64_t)idxv >= N) {
+        atomicOr(err_flag, 8);
+        idxv = -1;
+      }
+    }
+  }
+
+  f32x16 acc[Cfg::TM][Cfg::TN];
+  zero_acc<Cfg>(acc);
+  gemm_tile<Cfg>(E + j0, kp, Xs, D, Bp / Cfg::BK, smem, acc);
+
+  // A window of WIN rows of W and v is kept in flight: the loads of row n+WIN are issued as soon
+  // as row n has been used, across the two halves.  (Native vector types: arrays of them stay in
+  // registers.)
+  f32x4 w[WIN][NC], v[WIN][NC];
+  auto request = [&](int n) {
+    const int64_t row = __builtin_amdgcn_readlane(idxv, n);   // wave-uniform
+    const int64_t off = (row >= 0 ? row : 0) * D + lane * 4;  // row 0 stands in for a missing row
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      w[n % WIN][c] = *reinterpret_cast<const f32x4*>(W + off + c * 256);
+      v[n % WIN][c] = *reinterpret_cast<const f32x4*>(V + off + c * 256);
+    }
+  };
+#pragma unroll
+  for (int n = 0; n < WIN; ++n) request(n);
+
+  float* stage = reinterpret_cast<float*>(smem);
+  const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
+#pragma unroll
+  for (int h = 0; h < Cfg::WM; ++h) {
+    if (wm == h) {
+#pragma unroll
+      for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = bm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+#pragma unroll
+          for (int bn = 0; bn < Cfg::TN; ++bn)
+            stage[row * SROW + wn * Cfg::WTN + bn * 32 + (lane & 31)] = acc[bm][bn][r];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < RPW; ++q) {
+      const int n = h * RPW + q;
+      const int64_t row = __builtin_amdgcn_readlane(idxv, n);
+      const int hd = __builtin_amdgcn_readlane(headv, n);
+      const int r = q * WAVES + wave;
+      f32x4 g[NC];
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int d = c * 256 + lane * 4;
+        g[c] = *reinterpret_cast<const f32x4*>(stage + r * SROW + d);
+        if (hd != INT_MAX)   // first sample of a class in the batch: add the label part
+          g[c] += *reinterpret_cast<const f32x4*>(lab + (int64_t)hd * D + d);
+      }
+      float ww = 0.f, gw = 0.f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const f32x4 wc = w[n % WIN][c];
+        ww += wc[0] * wc[0] + wc[1] * wc[1] + wc[2] * wc[2] + wc[3] * wc[3];
+        gw += g[c][0] * wc[0] + g[c][1] * wc[1] + g[c][2] * wc[2] + g[c][3] * wc[3];
+      }
+      ww = wave_sum(ww);
+      gw = wave_sum(gw);
+      const float rn = 1.f / fmaxf(sqrtf(ww), 1e-12f);
+      const float t = gw * rn * rn;
+      if (row >= 0) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          const int d = c * 256 + lane * 4;
+          const f32x4 wc = w[n % WIN][c], vc = v[n % WIN][c];
+          f32x4 vn, wq;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            vn[e] = mu * vc[e] + (g[c][e] - t * wc[e]) * rn;
+            wq[e] = wc[e] - lr * vn[e];
+          }
+          *reinterpret_cast<f32x4*>(V + row * D + d) = vn;
+          *reinterpret_cast<f32x4*>(W + row * D + d) = wq;
+        }
+      }
+      if (n + WIN < ROWS) request(n + WIN);
+    }
+    __syncthreads();   // the next half overwrites the staged rows
   }
 }
 
@@ -659,12 +799,28 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
+// Number of batch slices of the dweight GEMM (1: none): slices only when the tiles alone leave
+// most CUs idle, limited by the room in the split buffer and by a minimum slice length.
+template <class CfgW>
+int dweight_slices(const pfc_ctx* c, int tiles, int Bp, int64_t kp) {
+  const int slabs_total = Bp / CfgW::BK;
+  int want = c->num_cu / tiles;
+  const int64_t room = (int64_t)kMaxSplits * Bp / kp;
+  if (want > room) want = (int)room;
+  if (want > slabs_total / 8) want = slabs_total / 8;   // a slice must stay long enough to pay
+                                                        // for its own partial tile
+  return want < 1 ? 1 : want;
+}
+
 template <typename T, int NC>
 int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t k,
         const int32_t* yl, int32_t B, const LossParams& lp, float* loss_out, float* dX_out,
-        float* dW_out, float* stats_out) {
+        float* dW_out, float* stats_out, const UpdateArgs* upd) {
   using CfgF = TileCfg<T, 256, 256, 2, 4, false, false>;   // logits: 256 classes x 256 samples
   using CfgW = TileCfg<T, 256, 256, 2, 4, true, true>;     // dweight: 256 classes x 256 of D
+  // fused dweight + update: 128 classes x all 512 columns, half-size slabs so that the wide
+  // operand fits; only used when D == 512
+  using CfgU = TileCfg<T, 128, 512, 2, 4, true, true, 64>;
   using CfgX = TileCfg<T, 256, 256, 2, 4, false, true>;    // dfeatures: 256 samples x 256 of D
   const int D = c->D;
   const int Bp = (int)round_up(B, kPadB);
@@ -691,6 +847,9 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_dfeatures_kernel<CfgX>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgX::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_update_kernel<CfgU>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                FusedUpdateLds<CfgU>::LDS));
     attr_done = true;
   }
   {
@@ -705,16 +864,13 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                tiles_j, B, Bp, D, X, c->rnormX, c->clabel, lp, c->rowmaxpart, c->rowscale,
                c->dlabel, c->lossrow, c->rowmax, yl, k, c->head, Xs);
   }
-  {
+  // dweight (+ label part) into dW_out
+  auto launch_dweight = [&]() -> int {
     const int tiles_j = (int)(kp / CfgW::BM), tiles_d = D / CfgW::BN;
     const int slabs_total = Bp / CfgW::BK;
     // slices of the batch when the tiles alone leave most CUs idle; the partial tiles borrow the
-    // dfeatures split buffer, which is not in use yet
-    int want = c->num_cu / (tiles_j * tiles_d);
-    const int64_t room = (int64_t)kMaxSplits * Bp / kp;
-    if (want > room) want = (int)room;
-    if (want > slabs_total / 8) want = slabs_total / 8;   // a slice must stay long enough to pay
-                                                          // for its own partial tile
+    // dfeatures split buffer, which is not in use at that point
+    const int want = dweight_slices<CfgW>(c, tiles_j * tiles_d, Bp, kp);
     if (want >= 2) {
       const int slabs_per = (slabs_total + want - 1) / want;
       const int nsp = (slabs_total + slabs_per - 1) / slabs_per;
@@ -729,11 +885,12 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                  dim3(xcd_grid(tiles_d, tiles_j)), dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs, D, k,
                  kp, Bp, dW_out, tiles_j, tiles_d, slabs_total, 1);
     }
-  }
-  PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel, dim3(B), dim3(kLabelThreads), 0, X, B, D, yl,
-             k, c->head, c->rnormX, c->dlabel, dW_out);
-  int splits;
-  {
+    PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel<false>, dim3(B), dim3(kLabelThreads), 0, X, B,
+               D, yl, k, c->head, c->rnormX, c->dlabel, dW_out);
+    return PFC_OK;
+  };
+  // dfeatures GEMM (split over S) + final reduction, projection, loss
+  auto launch_dfeatures = [&]() -> int {
     const int tiles_i = Bp / CfgX::BM, tiles_d = D / CfgX::BN;
     const int slabs_total = (int)(kp / CfgX::BK);
     int want = 256 / (tiles_i * tiles_d);
@@ -741,14 +898,38 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     if (want > kMaxSplits) want = kMaxSplits;
     if (want > slabs_total) want = slabs_total;
     const int slabs_per = (slabs_total + want - 1) / want;
-    splits = (slabs_total + slabs_per - 1) / slabs_per;
+    const int splits = (slabs_total + slabs_per - 1) / slabs_per;
     PFC_LAUNCH(c, KID_GEMM_DX, gemm_dfeatures_kernel<CfgX>,
                dim3(xcd_grid(tiles_i * tiles_d, splits)), dim3(CfgX::THREADS), CfgX::LDS_BYTES, E,
                Wn, D, Bp, kp, slabs_total, slabs_per, splits, c->dXpart, tiles_i, tiles_d);
+    PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3((B + 3) / 4 + 1), dim3(256), 0,
+               c->dXpart, splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW,
+               c->rowscale, c->dlabel, dX_out, c->lossrow, loss_out, c->clabel, c->rowmax,
+               stats_out);
+    return PFC_OK;
+  };
+
+  if (!upd) {
+    int rc = launch_dweight();
+    if (rc != PFC_OK) return rc;
+    return launch_dfeatures();
   }
-  PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3((B + 3) / 4 + 1), dim3(256), 0,
-             c->dXpart, splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW,
-             c->rowscale, c->dlabel, dX_out, c->lossrow, loss_out, c->clabel, c->rowmax, stats_out);
+  // Fused step.  dfeatures goes first: its final kernel reads the label rows of W, which the
+  // update is about to change.
+  int rc = launch_dfeatures();
+  if (rc != PFC_OK) return rc;
+  // one kernel only if D fits its tile and there is at least one tile per CU
+  const bool one_kernel = D == CfgU::BN && kp / CfgU::BM >= c->num_cu;
+  if (!one_kernel) {   // dWn through memory (dW_out is the context's own buffer here)
+    rc = launch_dweight();
+    if (rc != PFC_OK) return rc;
+    return update_impl(c, upd->W, upd->v, idx, k, dW_out, upd->lr, upd->mu);
+  }
+  PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel<true>, dim3(B), dim3(kLabelThreads), 0, X, B, D,
+             yl, k, c->head, c->rnormX, c->dlabel, c->dlab);
+  PFC_LAUNCH(c, KID_GEMM_DW_UPDATE, gemm_dweight_update_kernel<CfgU>, dim3((unsigned)(kp / CfgU::BM)),
+             dim3(CfgU::THREADS), FusedUpdateLds<CfgU>::LDS, E, Xs, k, kp, Bp, idx, c->head, c->dlab,
+             upd->W, upd->v, c->N, upd->lr, upd->mu, c->err_flag);
   return PFC_OK;
 }
 
@@ -757,7 +938,8 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
 int forward_backward_impl(pfc_ctx* c, const float* X, const float* W, const int32_t* idx,
                           int64_t k, const int32_t* yl, int32_t B, float s, float m,
                           int32_t margin_type, float filter_threshold, float* loss_out,
-                          float* dX_out, float* dW_out, float* stats_out) {
+                          float* dX_out, float* dW_out, float* stats_out,
+                          const UpdateArgs* upd) {
   LossParams lp;
   lp.s = s;
   lp.s_log2e = s * 1.44269504088896340736f;
@@ -768,7 +950,7 @@ int forward_backward_impl(pfc_ctx* c, const float* X, const float* W, const int3
   lp.tau = filter_threshold;
   lp.extras = (filter_threshold < 1.f || stats_out != nullptr) ? 1 : 0;
 #define PFC_RUN(T, NC) \
-  return run<T, NC>(c, X, W, idx, k, yl, B, lp, loss_out, dX_out, dW_out, stats_out)
+  return run<T, NC>(c, X, W, idx, k, yl, B, lp, loss_out, dX_out, dW_out, stats_out, upd)
   const int nc = c->D / 256;
   if (c->precision == PFC_PRECISION_BF16) {
     switch (nc) {

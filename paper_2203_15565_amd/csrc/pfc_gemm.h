@@ -41,31 +41,33 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kSlabBytes = 128;   // bytes of K per operand row per slab (k-contiguous layout)
 
 // Geometry of one operand slab in LDS.
-template <typename T, int R, bool KMAJOR>
+// SLAB: bytes of K per operand row per slab (128, or 64 for tiles whose wide operand would not fit).
+template <typename T, int R, bool KMAJOR, int SLAB>
 struct OperandLds {
-  static constexpr int BK = kSlabBytes / (int)sizeof(T);
+  static constexpr int SLAB_BYTES = SLAB;
+  static constexpr int BK = SLAB / (int)sizeof(T);
   static constexpr int ROWS = KMAJOR ? BK : R;                                   // LDS rows
-  static constexpr int ROW_BYTES = KMAJOR ? R * (int)sizeof(T) : kSlabBytes;     // payload
+  static constexpr int ROW_BYTES = KMAJOR ? R * (int)sizeof(T) : SLAB;     // payload
   static constexpr int STRIDE = ROW_BYTES + (KMAJOR ? 64 : 16);                  // padded
   static constexpr int BYTES = ROWS * STRIDE;
   static constexpr int CHUNKS_PER_ROW = ROW_BYTES / 16;
   static constexpr int CHUNKS = ROWS * CHUNKS_PER_ROW;                           // 16-byte chunks
 };
 
-template <typename T, int BM_, int BN_, int WM_, int WN_, bool AKM, bool BKM>
+template <typename T, int BM_, int BN_, int WM_, int WN_, bool AKM, bool BKM, int SLAB = 128>
 struct TileCfg {
   using elem = T;
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
   static constexpr bool A_KMAJOR = AKM, B_KMAJOR = BKM;
-  static constexpr int BK = kSlabBytes / (int)sizeof(T);   // reduction steps per slab
+  static constexpr int BK = SLAB / (int)sizeof(T);   // reduction steps per slab
+  static constexpr int GROUPS = SLAB / 32;           // reduction groups (fragment reads) per slab
   static constexpr int THREADS = WM * WN * 64;
   static constexpr int WTM = BM / WM, WTN = BN / WN;       // tile of one wavefront
   static constexpr int TM = WTM / 32, TN = WTN / 32;       // 32x32 blocks per wavefront
-  using LA = OperandLds<T, BM, AKM>;
-  using LB = OperandLds<T, BN, BKM>;
+  using LA = OperandLds<T, BM, AKM, SLAB>;
+  using LB = OperandLds<T, BN, BKM, SLAB>;
   static constexpr int A_BYTES = LA::BYTES, B_BYTES = LB::BYTES;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
@@ -119,7 +121,7 @@ struct Stager {
     base = reinterpret_cast<const char*>(tile);
     toff = (uint32_t)((int64_t)row * ld * (int64_t)sizeof(T) + ch * 16);
     pass = (int64_t)RPP * ld * (int64_t)sizeof(T);
-    slab = KMAJOR ? (int64_t)L::BK * ld * (int64_t)sizeof(T) : (int64_t)kSlabBytes;
+    slab = KMAJOR ? (int64_t)L::BK * ld * (int64_t)sizeof(T) : (int64_t)L::SLAB_BYTES;
     lds = row * L::STRIDE + ch * 16;
   }
   // The chunks of one slab live in ONE vector value (not an array), so they are registers by
@@ -214,8 +216,6 @@ __device__ __forceinline__ void mma_group(const Frags<Cfg>& f, f32x16 (&acc)[Cfg
     for (int bn = 0; bn < Cfg::TN; ++bn) mfma_group<T>(f.a[bm], f.b[bn], acc[bm][bn]);
 }
 
-constexpr int kGroups = kSlabBytes / 32;   // reduction groups (fragment reads) per slab
-
 // Accumulate acc += A_tile * B_tile^T over `nslabs` slabs of K.
 //   A: element (first of this workgroup's BM tile rows, first reduction step of its range)
 //   B: likewise for its BN tile rows;  lda / ldb in elements.
@@ -225,7 +225,7 @@ constexpr int kGroups = kSlabBytes / 32;   // reduction groups (fragment reads) 
 //     has had a whole iteration to arrive; it goes to the idle LDS stage at once, and the barrier
 //     at the end of the iteration publishes it;
 //   * the loads of slab s+2 then refill the registers, issued one at a time between the MFMAs of
-//     the first two groups: a wavefront that issues a whole slab in one burst queues up at the
+//     the first groups: a wavefront that issues a whole slab in one burst queues up at the
 //     memory pipe (measured: up to 1400 cycles) with its MFMAs stuck behind the loads;
 //   * inside a slab the fragments of group g+1 are read from LDS while group g is multiplied;
 //   * the last group of a slab is multiplied AFTER the barrier, behind the first fragment reads
@@ -254,8 +254,10 @@ __device__ __forceinline__ void gemm_tile(const typename Cfg::elem* __restrict__
   const int last = nslabs - 1;
   constexpr int NA = Cfg::A_CHUNKS, NL = Cfg::A_CHUNKS + Cfg::B_CHUNKS;
   constexpr int MM = Cfg::TM * Cfg::TN;            // MFMAs per group
-  constexpr int PER = (NL + 1) / 2;                // loads placed in each of the first two groups
-  static_assert(PER <= (MM + 1) / 2, "one load in front of every other MFMA at most");
+  constexpr int HEAD = Cfg::GROUPS - 1;            // groups multiplied before the barrier
+  // the loads of a slab are placed in front of the MFMAs of the first one or two groups
+  constexpr int SPAN = (HEAD < 2 ? HEAD : 2) * MM;
+  static_assert(HEAD >= 1 && NL <= SPAN, "one load per MFMA slot at most");
 
   // prologue: slabs 0 and 1 are requested back to back; slab 0 goes to stage 0
   typename SA::Regs a0 = {};
@@ -279,16 +281,18 @@ __device__ __forceinline__ void gemm_tile(const typename Cfg::elem* __restrict__
     sb.store(nxt + Cfg::A_BYTES, b0);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int g = 0; g + 1 < kGroups; ++g) {
+    for (int g = 0; g < HEAD; ++g) {
       Frags<Cfg> fn;
       read_group<Cfg>(cur, g + 1, wm, wn, fn);
       __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs they do not feed
 #pragma unroll
       for (int q = 0; q < MM; ++q) {
-        const int li = g * PER + q / 2;    // chunk to request in front of this MFMA
-        if (g < 2 && (q & 1) == 0 && q / 2 < PER && li < NL) {
-          if (li < NA) sa.load_chunk(s2, li, a0);
-          else sb.load_chunk(s2, li - NA, b0);
+#pragma unroll
+        for (int c = 0; c < NL; ++c) {     // chunk c is requested in front of MFMA c*SPAN/NL
+          if (c * SPAN / NL == g * MM + q) {
+            if (c < NA) sa.load_chunk(s2, c, a0);
+            else sb.load_chunk(s2, c - NA, b0);
+          }
         }
         mfma_group<T>(fc.a[q / Cfg::TN], fc.b[q % Cfg::TN], acc[q / Cfg::TN][q % Cfg::TN]);
       }

@@ -1,0 +1,177 @@
+"""GPU parity of pfc_forward_backward_update (forward/backward and update in one call): against
+the oracle, and against the two separate calls it stands for."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import pfc_oracle as O
+from paper_2203_15565_amd import binding, workloads
+from pfc_harness import rel_max, row_rel_err
+from test_gpu_step import GRAD_TOL, LOSS_TOL, W_TOL, _device_weight, _run_steps
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def _torch():
+    import torch
+    return torch
+
+
+# (N, B, D, r, precision, label spread): D = 512 with enough classes takes the one-kernel form;
+# D = 256 and the small-k / large-batch case go through the context's gradient buffer.
+CASES = [
+    (10_000, 128, 512, 0.1, binding.PRECISION_FP32, 10_000),
+    (93_431, 512, 512, 0.1, binding.PRECISION_BF16, 93_431),
+    (20_000, 300, 512, 0.27, binding.PRECISION_BF16, 40),       # heavy duplicates, ragged B and k
+    (3_000, 100, 256, 0.1, binding.PRECISION_FP32, 3_000),      # D != 512
+    (50_000, 4096, 512, 1e-9, binding.PRECISION_BF16, 50_000),  # k = U small, batch sliced
+]
+
+
+@pytest.mark.parametrize("N,B,D,r,precision,spread", CASES)
+@pytest.mark.parametrize("options", [False, True])
+def test_fused_equals_two_calls(N, B, D, r, precision, spread, options):
+    torch = _torch()
+    rng = np.random.default_rng(77)
+    W0 = (rng.standard_normal((N, D)) * 0.01).astype(np.float32)
+    v0 = (rng.standard_normal((N, D)) * 1e-3).astype(np.float32)
+    X = rng.standard_normal((B, D)).astype(np.float32)
+    labels = rng.permutation(N)[:spread][rng.integers(0, spread, size=B)].astype(np.int64)
+    s, m, lr, mu = 64.0, 0.5, 0.1, 0.9
+    margin = binding.MARGIN_COSFACE if options else binding.MARGIN_ARCFACE
+    tau = 0.05 if options else 2.0
+    if options:
+        m = 0.35
+    out = {}
+    for fused in (False, True):
+        _say("fused vs two calls", N, B, D, r, precision, spread, options, "fused" if fused else "split")
+        ctx = binding.Context(N, D, B, r, precision)
+        Wd, vd = torch.from_numpy(W0).cuda(), torch.from_numpy(v0).cuda()
+        cap = binding.pfc_num_sampled(N, B, r)
+        idx = torch.zeros(cap, dtype=torch.int32, device="cuda")
+        yl = torch.zeros(B, dtype=torch.int32, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        dX = torch.zeros(B, D, device="cuda")
+        stats = torch.zeros(2, device="cuda") if options else None
+        Xd, ld = torch.from_numpy(X).cuda(), torch.from_numpy(labels).cuda()
+        k = ctx.pfc_sample(ld, r, 3, 5, idx, yl)
+        if fused:
+            ctx.pfc_forward_backward_update(Xd, Wd, vd, idx, k, yl, s, m, lr, mu, loss, dX,
+                                            margin_type=margin, filter_threshold=tau,
+                                            stats_out=stats)
+        else:
+            dW = torch.zeros(cap, D, device="cuda")
+            ctx.pfc_forward_backward_ex(Xd, Wd, idx, k, yl, s, m, margin, tau, loss, dX, dW, stats)
+            ctx.pfc_update(Wd, vd, idx, k, dW, lr, mu)
+        torch.cuda.synchronize()
+        assert ctx.pfc_check() == binding.PFC_OK
+        out[fused] = (Wd.cpu().numpy(), vd.cpu().numpy(), float(loss.item()), dX.cpu().numpy(),
+                      None if stats is None else stats.cpu().numpy(), idx[:k].cpu().numpy())
+        ctx.close()
+    Wa, va, la, dXa, sa, ia = out[False]
+    Wb, vb, lb, dXb, sb, ib = out[True]
+    assert np.array_equal(ia, ib)
+    # loss, feature gradient and statistics come from the same kernels on the same inputs
+    assert la == lb
+    assert dXa.tobytes() == dXb.tobytes()
+    if options:
+        assert sa.tobytes() == sb.tobytes()
+    # rows outside the sample: untouched by both
+    mask = np.ones(N, dtype=bool)
+    mask[ia] = False
+    assert Wb[mask].tobytes() == W0[mask].tobytes() and vb[mask].tobytes() == v0[mask].tobytes()
+    # sampled rows: same arithmetic up to the summation order inside the GEMM tiles
+    sel = ia.astype(np.int64)
+    assert not np.array_equal(Wb[sel], W0[sel])
+    nrm = np.linalg.norm(Wa[sel].astype(np.float64), axis=1)
+    err = row_rel_err(Wb[sel], Wa[sel], nrm)
+    _say("   W row diff fused vs two calls", err, "identical" if Wa.tobytes() == Wb.tobytes() else "")
+    assert err <= 1e-6
+    assert rel_max(vb[sel], va[sel]) <= 1e-5
+
+
+def test_fused_tiny_workload_step():
+    _run_steps(workloads.CONFIGS["tiny"], 1, fused=True)
+
+
+def test_fused_medium_workload_ten_steps():
+    _run_steps(workloads.CONFIGS["medium"], 10, fused=True)
+
+
+def test_fused_einval():
+    torch = _torch()
+    N, B, D = 2000, 64, 512
+    ctx = binding.Context(N, D, B, 0.1, binding.PRECISION_FP32)
+    W = torch.zeros(N, D, device="cuda")
+    v = torch.zeros(N, D, device="cuda")
+    X = torch.zeros(B, D, device="cuda")
+    idx = torch.arange(200, dtype=torch.int32, device="cuda")
+    yl = torch.zeros(B, dtype=torch.int32, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    dX = torch.zeros(B, D, device="cuda")
+    good = dict(s=64.0, m=0.5, lr=0.1, mu=0.9)
+    for bad in (dict(s=65.0), dict(s=0.0), dict(m=-0.1), dict(lr=float("nan")), dict(mu=float("nan"))):
+        kw = dict(good, **bad)
+        with pytest.raises(binding.PfcError):
+            ctx.pfc_forward_backward_update(X, W, v, idx, 200, yl, kw["s"], kw["m"], kw["lr"],
+                                            kw["mu"], loss, dX)
+    with pytest.raises(binding.PfcError):
+        ctx.pfc_forward_backward_update(X, W, v, idx, 0, yl, 64.0, 0.5, 0.1, 0.9, loss, dX)
+    with pytest.raises(binding.PfcError):
+        ctx.pfc_forward_backward_update(X, W, v, idx, 200, yl, 64.0, 0.5, 0.1, 0.9, loss, dX,
+                                        margin_type=7)
+    ctx.close()
+
+
+def test_fused_full_size_headline_step():
+    """One fused step at the headline size against the oracle run on the sampled rows."""
+    torch = _torch()
+    wl = workloads.CONFIGS["headline"]
+    Wd = _device_weight(wl)
+    W_before = Wd.clone()
+    vd = torch.zeros_like(Wd)
+    ctx = binding.Context(wl.N, wl.D, wl.B, wl.r, wl.precision)
+    cap = binding.pfc_num_sampled(wl.N, wl.B, wl.r)
+    idx_d = torch.zeros(cap, dtype=torch.int32, device="cuda")
+    yl_d = torch.zeros(wl.B, dtype=torch.int32, device="cuda")
+    loss_d = torch.zeros(1, device="cuda")
+    dX_d = torch.zeros(wl.B, wl.D, device="cuda")
+    X = workloads.make_features(wl, 0)
+    labels = workloads.make_labels(wl, 0)
+    labels_d = torch.from_numpy(labels).cuda()
+    X_d = torch.from_numpy(X).cuda()
+    _say("fused full size step")
+    k = ctx.pfc_sample(labels_d, wl.r, wl.seed, 0, idx_d, yl_d)
+    ctx.pfc_forward_backward_update(X_d, Wd, vd, idx_d, k, yl_d, wl.s, wl.m, wl.lr, wl.mu, loss_d,
+                                    dX_d)
+    torch.cuda.synchronize()
+    assert ctx.pfc_check() == binding.PFC_OK
+    oidx, oyl, ok = O.sample(labels, wl.N, wl.r, wl.seed, 0)
+    assert k == ok and np.array_equal(idx_d[:k].cpu().numpy(), oidx)
+    sel = torch.from_numpy(oidx.astype(np.int64)).cuda()
+    W_S = W_before[sel].cpu().numpy()
+    o = O.forward_backward(X, W_S, oyl, wl.s, wl.m)
+    gl = float(loss_d.item())
+    assert abs(gl - o["loss"]) <= LOSS_TOL[wl.precision] * abs(o["loss"])
+    assert rel_max(dX_d.cpu().numpy(), o["dX"]) <= GRAD_TOL[wl.precision]
+    W_S64 = W_S.astype(np.float64)
+    v_S64 = np.zeros_like(W_S64)
+    O.update(W_S64, v_S64, np.arange(k), o["dW"], wl.lr, wl.mu)
+    err = row_rel_err(Wd[sel].cpu().numpy(), W_S64, np.linalg.norm(W_S64, axis=1))
+    _say("   loss", gl, o["loss"], "W row err", err)
+    assert err <= W_TOL
+    assert rel_max(vd[sel].cpu().numpy(), v_S64) <= GRAD_TOL[wl.precision]
+    mask = torch.ones(wl.N, dtype=torch.bool, device="cuda")
+    mask[sel] = False
+    same = (Wd.view(torch.int32) == W_before.view(torch.int32)).all(dim=1)
+    assert bool(same[mask].all())
+    assert not bool(vd[mask].any())
+    assert not bool(same[~mask].all())
+    ctx.close()

@@ -150,8 +150,9 @@ def test_update_parity_and_untouched_rows():
     ctx.close()
 
 
-def _run_steps(wl, nsteps, check_every_step=True):
-    """Whole steps sample -> forward/backward -> update on the GPU next to the oracle."""
+def _run_steps(wl, nsteps, check_every_step=True, fused=False):
+    """Whole steps sample -> forward/backward -> update on the GPU next to the oracle
+    (fused: forward/backward and update in the one call pfc_forward_backward_update)."""
     torch = _torch()
     W0 = workloads.make_weight(wl)
     W64, v64 = W0.astype(np.float64), np.zeros(W0.shape)
@@ -172,8 +173,12 @@ def _run_steps(wl, nsteps, check_every_step=True):
         labels_d = torch.from_numpy(labels).cuda()      # referenced until the synchronize below
         X_d = torch.from_numpy(X).cuda()
         k = ctx.pfc_sample(labels_d, wl.r, wl.seed, t, idx_d, yl_d)
-        ctx.pfc_forward_backward(X_d, Wd, idx_d, k, yl_d, wl.s, wl.m, loss_d, dX_d, dW_d)
-        ctx.pfc_update(Wd, vd, idx_d, k, dW_d, wl.lr, wl.mu)
+        if fused:
+            ctx.pfc_forward_backward_update(X_d, Wd, vd, idx_d, k, yl_d, wl.s, wl.m, wl.lr, wl.mu,
+                                            loss_d, dX_d)
+        else:
+            ctx.pfc_forward_backward(X_d, Wd, idx_d, k, yl_d, wl.s, wl.m, loss_d, dX_d, dW_d)
+            ctx.pfc_update(Wd, vd, idx_d, k, dW_d, wl.lr, wl.mu)
         torch.cuda.synchronize()
         assert ctx.pfc_check() == binding.PFC_OK
         oloss, odX, oidx, oyl, fb = O.step(X, labels, W64, v64, r=wl.r, s=wl.s, m=wl.m, lr=wl.lr,
