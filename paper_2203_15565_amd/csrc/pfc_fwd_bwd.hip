@@ -565,9 +565,10 @@ struct FusedUpdateLds {
 };
 
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_update_kernel(
-    const typename Cfg::elem* __restrict__ E, const typename Cfg::elem* __restrict__ Xs, int64_t k,
-    int64_t kp, int Bp, const int32_t* __restrict__ idx, const int32_t* __restrict__ head,
+__device__ __forceinline__ void fused_update_tile(
+    int64_t j0, char* smem, const typename Cfg::elem* __restrict__ E,
+    const typename Cfg::elem* __restrict__ Xs, int64_t k, int64_t kp, int Bp,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ head,
     const float* __restrict__ lab, float* __restrict__ W, float* __restrict__ V, int64_t N,
     float lr, float mu, int32_t* __restrict__ err_flag) {
   using FL = FusedUpdateLds<Cfg>;
@@ -576,9 +577,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_update_kernel(
   constexpr int ROWS = Cfg::WM * RPW;                           // rows per wavefront and tile
   constexpr int WIN = 4;                                        // rows of W and v in flight
   static_assert(D % 256 == 0 && HR % WAVES == 0 && ROWS <= 64 && WIN <= ROWS, "fused update geometry");
-  extern __shared__ __align__(16) char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t j0 = (int64_t)blockIdx.x * Cfg::BM;
 
   // Row n of this wavefront (n = h*RPW + q) is tile row h*HR + q*WAVES + wave: neighbouring
   // wavefronts take neighbouring rows.  Lane n fetches its class id and label head now, so that
@@ -676,6 +675,27 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_update_kernel(
     }
     __syncthreads();   // the next half overwrites the staged rows
   }
+}
+
+// The first n_big workgroups take tiles of CfgB::BM rows; the rows left over when those no longer
+// fill a whole round of workgroups on the GPU go to the following workgroups in tiles of
+// CfgS::BM rows, so that the last, partly filled round is short.
+template <class CfgB, class CfgS>
+__global__ __launch_bounds__(CfgB::THREADS) void gemm_dweight_update_kernel(
+    const typename CfgB::elem* __restrict__ E, const typename CfgB::elem* __restrict__ Xs,
+    int64_t k, int64_t kp, int Bp, const int32_t* __restrict__ idx,
+    const int32_t* __restrict__ head, const float* __restrict__ lab, float* __restrict__ W,
+    float* __restrict__ V, int64_t N, float lr, float mu, int32_t* __restrict__ err_flag,
+    int n_big) {
+  static_assert(CfgB::THREADS == CfgS::THREADS && CfgB::BN == CfgS::BN, "one launch shape");
+  extern __shared__ __align__(16) char smem[];
+  const int b = blockIdx.x;
+  if (b < n_big)
+    fused_update_tile<CfgB>((int64_t)b * CfgB::BM, smem, E, Xs, k, kp, Bp, idx, head, lab, W, V,
+                            N, lr, mu, err_flag);
+  else
+    fused_update_tile<CfgS>((int64_t)n_big * CfgB::BM + (int64_t)(b - n_big) * CfgS::BM, smem, E,
+                            Xs, k, kp, Bp, idx, head, lab, W, V, N, lr, mu, err_flag);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -821,7 +841,11 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   // fused dweight + update: 128 classes x all 512 columns, half-size slabs so that the wide
   // operand fits; only used when D == 512
   using CfgU = TileCfg<T, 128, 512, 2, 4, true, true, 64>;
+  using CfgUS = TileCfg<T, 64, 512, 1, 8, true, true, 128>;   // its tiles for the last round
   using CfgX = TileCfg<T, 256, 256, 2, 4, false, true>;    // dfeatures: 256 samples x 256 of D
+  constexpr int kFusedLds = FusedUpdateLds<CfgU>::LDS > FusedUpdateLds<CfgUS>::LDS
+                                ? FusedUpdateLds<CfgU>::LDS : FusedUpdateLds<CfgUS>::LDS;
+  static_assert(kFusedLds <= 160 * 1024, "LDS of one compute unit");
   const int D = c->D;
   const int Bp = (int)round_up(B, kPadB);
   const int64_t kp = round_up(k, kPadK);
@@ -847,9 +871,8 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_dfeatures_kernel<CfgX>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgX::LDS_BYTES));
-    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_update_kernel<CfgU>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                FusedUpdateLds<CfgU>::LDS));
+    PFC_HIP(hipFuncSetAttribute((const void*)(gemm_dweight_update_kernel<CfgU, CfgUS>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLds));
     attr_done = true;
   }
   {
@@ -927,9 +950,14 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   }
   PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel<true>, dim3(B), dim3(kLabelThreads), 0, X, B, D,
              yl, k, c->head, c->rnormX, c->dlabel, c->dlab);
-  PFC_LAUNCH(c, KID_GEMM_DW_UPDATE, gemm_dweight_update_kernel<CfgU>, dim3((unsigned)(kp / CfgU::BM)),
-             dim3(CfgU::THREADS), FusedUpdateLds<CfgU>::LDS, E, Xs, k, kp, Bp, idx, c->head, c->dlab,
-             upd->W, upd->v, c->N, upd->lr, upd->mu, c->err_flag);
+  {
+    const int tiles_big = (int)(kp / CfgU::BM);
+    const int n_big = tiles_big / c->num_cu * c->num_cu;          // whole rounds
+    const int n_small = (tiles_big - n_big) * (CfgU::BM / CfgUS::BM);
+    PFC_LAUNCH(c, KID_GEMM_DW_UPDATE, (gemm_dweight_update_kernel<CfgU, CfgUS>),
+               dim3((unsigned)(n_big + n_small)), dim3(CfgU::THREADS), kFusedLds, E, Xs, k, kp, Bp,
+               idx, c->head, c->dlab, upd->W, upd->v, c->N, upd->lr, upd->mu, c->err_flag, n_big);
+  }
   return PFC_OK;
 }
 

@@ -255,8 +255,9 @@ __device__ __forceinline__ void gemm_tile(const typename Cfg::elem* __restrict__
   constexpr int NA = Cfg::A_CHUNKS, NL = Cfg::A_CHUNKS + Cfg::B_CHUNKS;
   constexpr int MM = Cfg::TM * Cfg::TN;            // MFMAs per group
   constexpr int HEAD = Cfg::GROUPS - 1;            // groups multiplied before the barrier
-  // the loads of a slab are placed in front of the MFMAs of the first one or two groups
-  constexpr int SPAN = (HEAD < 2 ? HEAD : 2) * MM;
+  // the loads of a slab are placed in front of the MFMAs of the first one or two groups (of all
+  // groups before the barrier if two do not have an MFMA for each load)
+  constexpr int SPAN = (NL <= 2 * MM ? (HEAD < 2 ? HEAD : 2) : HEAD) * MM;
   static_assert(HEAD >= 1 && NL <= SPAN, "one load per MFMA slot at most");
 
   // prologue: slabs 0 and 1 are requested back to back; slab 0 goes to stage 0

@@ -24,12 +24,15 @@ def _torch():
     return torch
 
 
-# (N, B, D, r, precision, label spread): D = 512 with enough classes takes the one-kernel form;
-# D = 256 and the small-k / large-batch case go through the context's gradient buffer.
+# (N, B, D, r, precision, label spread).  D = 512 with at least one 128-row tile per compute unit
+# (k >= 32K on a 256-CU GPU) takes the one-kernel form, the rows beyond the last whole round of
+# tiles going to half-height tiles; everything else goes through the context's gradient buffer.
 CASES = [
-    (10_000, 128, 512, 0.1, binding.PRECISION_FP32, 10_000),
+    (400_000, 300, 512, 0.1, binding.PRECISION_BF16, 400_000),  # one kernel, ragged B, k and tail
+    (400_000, 300, 512, 0.1, binding.PRECISION_FP32, 60),       # one kernel, heavy duplicates
+    (327_680, 256, 512, 0.1, binding.PRECISION_BF16, 327_680),  # one kernel, k = 32768: no tail
+    (10_000, 128, 512, 0.1, binding.PRECISION_FP32, 10_000),    # too few tiles
     (93_431, 512, 512, 0.1, binding.PRECISION_BF16, 93_431),
-    (20_000, 300, 512, 0.27, binding.PRECISION_BF16, 40),       # heavy duplicates, ragged B and k
     (3_000, 100, 256, 0.1, binding.PRECISION_FP32, 3_000),      # D != 512
     (50_000, 4096, 512, 1e-9, binding.PRECISION_BF16, 50_000),  # k = U small, batch sliced
 ]
@@ -103,6 +106,11 @@ def test_fused_tiny_workload_step():
 
 def test_fused_medium_workload_ten_steps():
     _run_steps(workloads.CONFIGS["medium"], 10, fused=True)
+
+
+def test_fused_large_workload_steps():
+    # 36,024 sampled classes: the one-kernel form, with a last round of half-height tiles
+    _run_steps(workloads.CONFIGS["large"], 3, check_every_step=False, fused=True)
 
 
 def test_fused_einval():
