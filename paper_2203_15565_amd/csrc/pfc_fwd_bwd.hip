@@ -770,9 +770,38 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
     }
     return;
   }
-  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (i >= B) return;
+  // One workgroup per sample.  The four wavefronts share the slices of S (wavefront w takes
+  // slices w, w+4, ...: several independent loads in flight each); their partial rows are added
+  // in wavefront order by wavefront 0, which then finishes the row: the same order on every run.
+  const int i = blockIdx.x;
+  const int wave = threadIdx.x >> 6;
   constexpr int nchunk = NC;
+  __shared__ float4 s_part[3][NC][64];
+  float4 sum[NC];
+#pragma unroll
+  for (int c = 0; c < nchunk; ++c) sum[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int sp = wave; sp < splits; sp += 4) {
+#pragma unroll
+    for (int c = 0; c < nchunk; ++c) {
+      const float4 t = *reinterpret_cast<const float4*>(part + ((int64_t)sp * Bp + i) * D +
+                                                        c * 256 + lane * 4);
+      sum[c].x += t.x; sum[c].y += t.y; sum[c].z += t.z; sum[c].w += t.w;
+    }
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int c = 0; c < nchunk; ++c) s_part[wave - 1][c][lane] = sum[c];
+  }
+  __syncthreads();
+  if (wave > 0) return;
+#pragma unroll
+  for (int c = 0; c < nchunk; ++c) {
+#pragma unroll
+    for (int w = 0; w < 3; ++w) {
+      const float4 t = s_part[w][c][lane];
+      sum[c].x += t.x; sum[c].y += t.y; sum[c].z += t.z; sum[c].w += t.w;
+    }
+  }
   const float rs = rowscale[i], rnx = rnormX[i], dl = dlabel[i];
   const int32_t y = yl[i];
   int64_t wrow = -1;
@@ -787,11 +816,7 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
 #pragma unroll
   for (int c = 0; c < nchunk; ++c) {
     const int d = c * 256 + lane * 4;
-    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int sp = 0; sp < splits; ++sp) {
-      const float4 t = *reinterpret_cast<const float4*>(part + ((int64_t)sp * Bp + i) * D + d);
-      a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
-    }
+    float4 a = sum[c];
     a.x *= rs; a.y *= rs; a.z *= rs; a.w *= rs;
     if (wrow >= 0) {
       const float4 w = *reinterpret_cast<const float4*>(W + wrow * D + d);
@@ -925,7 +950,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     PFC_LAUNCH(c, KID_GEMM_DX, gemm_dfeatures_kernel<CfgX>,
                dim3(xcd_grid(tiles_i * tiles_d, splits)), dim3(CfgX::THREADS), CfgX::LDS_BYTES, E,
                Wn, D, Bp, kp, slabs_total, slabs_per, splits, c->dXpart, tiles_i, tiles_d);
-    PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3((B + 3) / 4 + 1), dim3(256), 0,
+    PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3(B + 1), dim3(256), 0,
                c->dXpart, splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW,
                c->rowscale, c->dlabel, dX_out, c->lossrow, loss_out, c->clabel, c->rowmax,
                stats_out);
