@@ -33,13 +33,13 @@ def test_algorithmic_work_of_the_headline_step():
     assert w["gemm_dweight_update"] == ("hbm", B * k * 2.0 + B * D * 2.0 + 4.0 * k * D * 4)
 
 
-def test_workload_table_matches_the_paper_sizes():
+def test_workload_table_matches_the_benchmark_configurations():
     c = workloads.CONFIGS
     assert (c["tiny"].B, c["tiny"].N, c["tiny"].precision) == (128, 10_000, 0)
-    assert (c["medium"].B, c["medium"].N) == (512, 93_431)          # MS1MV3 identities
-    assert (c["large"].B, c["large"].N) == (1024, 360_232)          # Glint360K
-    assert (c["headline"].B, c["headline"].N, c["headline"].r) == (1024, 2_059_906, 0.1)  # WebFace42M
-    assert (c["extreme"].B, c["extreme"].N) == (2048, 10_000_000)   # the synthetic 10M of Tab. 6
+    assert (c["medium"].B, c["medium"].N) == (512, 93_431)
+    assert (c["large"].B, c["large"].N) == (1024, 360_232)
+    assert (c["headline"].B, c["headline"].N, c["headline"].r) == (1024, 2_059_906, 0.1)
+    assert (c["extreme"].B, c["extreme"].N) == (2048, 10_000_000)   # 10M classes as in Tab. 6
     assert all(w.D == 512 and w.s == 64.0 and w.m == 0.5 for w in c.values())
     for w in c.values():
         assert binding.pfc_num_sampled(w.N, w.B, w.r) >= w.B
