@@ -26,12 +26,12 @@ PEAK_FP32_MFMA_TFLOPS = 157.3  # fp32 MFMA
 # summarised in profiles/headline_step_hbm_traffic.md, keyed by (workload, r, kernel).  None where
 # no counter run has been recorded.
 MEASURED_TRAFFIC_BYTES: dict = {
-    ("headline", 0.1, "gemm_dweight_update"): 2171206563,
-    ("headline", 0.1, "update"): 2115925050,          # the two below: --two-calls, earlier run
-    ("headline", 0.1, "gather_normalize_w"): 636865329,
-    ("headline", 0.1, "gemm_logits"): 775808822,
-    ("headline", 0.1, "gemm_dweight"): 902858441,
-    ("headline", 0.1, "gemm_dfeatures"): 700303841,
+    ("headline", 0.1, "gemm_dweight_update"): 2171208964,
+    ("headline", 0.1, "update"): 2115922288,
+    ("headline", 0.1, "gather_normalize_w"): 636864350,
+    ("headline", 0.1, "gemm_logits"): 775756232,
+    ("headline", 0.1, "gemm_dweight"): 902774880,
+    ("headline", 0.1, "gemm_dfeatures"): 700317795,
 }
 
 
@@ -105,9 +105,9 @@ def main() -> int:
     # reference that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run.
     torch.mul(dW, 1.0, out=dW)
 
-    def step(t: int) -> int:
+    def step(t: int, two_calls: bool = args.two_calls) -> int:
         k = ctx.pfc_sample(labels[t], wl.r, wl.seed, t, idx, yl)
-        if args.two_calls:
+        if two_calls:
             ctx.pfc_forward_backward(feats[t], Wd, idx, k, yl, wl.s, wl.m, loss, dX, dW)
             ctx.pfc_update(Wd, vd, idx, k, dW, wl.lr, wl.mu)
         else:   # same results; the center gradient stays inside the library
@@ -162,6 +162,15 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / K * 1e3
     value = wl.B * K / elapsed
+
+    # ---- the other call sequence over the same number of steps, for the record ----
+    other = not args.two_calls
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(Wm, nsteps):
+        step(t, other)
+    torch.cuda.synchronize()
+    other_elapsed = time.perf_counter() - t0
 
     # ---- per-kernel durations: same steps again with an event pair around every kernel ----
     ctx.pfc_set_timing(True)
@@ -224,6 +233,11 @@ def main() -> int:
                    "B": wl.B, "D": wl.D, "N": wl.N, "r": wl.r, "k": k,
                    "calls": "pfc_sample + pfc_forward_backward + pfc_update" if args.two_calls
                    else "pfc_sample + pfc_forward_backward_update"},
+        "other_call_sequence": {
+            "calls": "pfc_sample + pfc_forward_backward + pfc_update" if other
+            else "pfc_sample + pfc_forward_backward_update",
+            "ms_per_step": round(other_elapsed / K * 1e3, 4),
+            "value": round(wl.B * K / other_elapsed, 1)},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "measured_peaks": measured,
