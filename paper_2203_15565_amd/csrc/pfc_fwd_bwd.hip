@@ -676,8 +676,10 @@ __device__ __forceinline__ void fused_update_tile(
             vn[e] = mu * vc[e] + (g[c][e] - t * wc[e]) * rn;
             wq[e] = wc[e] - lr * vn[e];
           }
-          *reinterpret_cast<f32x4*>(V + row * D + d) = vn;
-          *reinterpret_cast<f32x4*>(W + row * D + d) = wq;
+          // not read again before the next step's gather: nontemporal, so that the rows do not
+          // sit dirty in the L2 while the next kernels run
+          __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(V + row * D + d));
+          __builtin_nontemporal_store(wq, reinterpret_cast<f32x4*>(W + row * D + d));
         }
       }
       if (n + WIN < ROWS) request(n + WIN);
