@@ -26,12 +26,12 @@ PEAK_FP32_MFMA_TFLOPS = 157.3  # fp32 MFMA
 # summarised in profiles/headline_step_hbm_traffic.md, keyed by (workload, r, kernel).  None where
 # no counter run has been recorded.
 MEASURED_TRAFFIC_BYTES: dict = {
-    ("headline", 0.1, "gemm_dweight_update"): 2171208964,
-    ("headline", 0.1, "update"): 2115922288,
-    ("headline", 0.1, "gather_normalize_w"): 636864350,
-    ("headline", 0.1, "gemm_logits"): 775756232,
-    ("headline", 0.1, "gemm_dweight"): 902774880,
-    ("headline", 0.1, "gemm_dfeatures"): 700317795,
+    ("headline", 0.1, "gemm_dweight_update"): 2171192260,
+    ("headline", 0.1, "update"): 2115921901,
+    ("headline", 0.1, "gather_normalize_w"): 636325933,
+    ("headline", 0.1, "gemm_logits"): 679896561,
+    ("headline", 0.1, "gemm_dweight"): 902788764,
+    ("headline", 0.1, "gemm_dfeatures"): 700277303,
 }
 
 
