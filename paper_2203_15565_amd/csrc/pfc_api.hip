@@ -16,8 +16,8 @@ void set_hip_error(hipError_t e, const char* what) {
 }
 
 static const char* const kKernelNames[KID_COUNT] = {
-    "sample_init",   "sample_mark",  "sample_hist0", "sample_scan0", "sample_hist1",
-    "sample_scan1",  "sample_hist2", "sample_scan2", "sample_count", "sample_blkscan",
+    "sample_mark",  "sample_hist0", "sample_scan0", "sample_hist1",
+    "sample_scan1",  "sample_hist2", "sample_scan2", "sample_count",
     "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_logits",
     "row_combine",   "gemm_dweight", "dweight_reduce", "dweight_label",
     "gemm_dfeatures", "dfeatures_final", "update", "gemm_dweight_update"};
@@ -65,7 +65,7 @@ static int dev_alloc(void** p, size_t bytes) {
 int pfc_destroy(pfc_ctx* c) {
   if (!c) return PFC_EINVAL;
   (void)hipStreamSynchronize(c->stream);
-  void* bufs[] = {c->pos_bits, c->hist, c->sel, c->blk_cnt, c->blk_off, c->err_flag, c->Xn,
+  void* bufs[] = {c->pos_bits, c->hist, c->sel, c->blk_cnt, c->err_flag, c->Xn,
                   c->Xs, c->rnormX, c->Wn, c->rnormW, c->head, c->E, c->rowpart, c->rowmaxpart, c->rowmax,
                   c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart, c->dlab, c->dWtmp};
   for (void* b : bufs)
@@ -121,7 +121,6 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(hist, 3 * 4096 * 4);
   ALLOC(sel, sizeof(SelState));
   ALLOC(blk_cnt, (size_t)c->nblk_cap * 2 * 4);
-  ALLOC(blk_off, (size_t)c->nblk_cap * 2 * 4);
   ALLOC(err_flag, 16);
   ALLOC(Xn, Bp * Dz * es);
   ALLOC(Xs, Bp * Dz * es);
@@ -146,6 +145,16 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
     if (e != hipSuccess) {
       set_hip_error(e, "hipHostMalloc");
       rc = PFC_ENOMEM;
+    }
+  }
+  // the sampler keeps its scratch all zero between calls (every last reader clears its piece)
+  if (rc == PFC_OK) {
+    hipError_t e = hipMemsetAsync(c->pos_bits, 0, ((size_t)(N + 31) / 32 + 64) * 4, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->hist, 0, 3 * 4096 * 4, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->sel, 0, sizeof(SelState), c->stream);
+    if (e != hipSuccess) {
+      set_hip_error(e, "hipMemsetAsync(sampler scratch)");
+      rc = PFC_EHIP;
     }
   }
   if (rc == PFC_OK) {

@@ -20,8 +20,7 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 // Kernel ids for the optional per-kernel timing.
 enum KernelId {
-  KID_SAMPLE_INIT = 0,
-  KID_SAMPLE_MARK,
+  KID_SAMPLE_MARK = 0,
   KID_SAMPLE_HIST0,
   KID_SAMPLE_SCAN0,
   KID_SAMPLE_HIST1,
@@ -29,7 +28,6 @@ enum KernelId {
   KID_SAMPLE_HIST2,
   KID_SAMPLE_SCAN2,
   KID_SAMPLE_COUNT,
-  KID_SAMPLE_BLKSCAN,
   KID_SAMPLE_WRITE,
   KID_SAMPLE_REMAP,
   KID_NORM_X,
@@ -77,7 +75,6 @@ struct pfc_ctx {
   uint32_t* hist;         // 3 x 4096 bins (radix passes of 8, 12 and 12 bits)
   pfc::SelState* sel;
   uint32_t* blk_cnt;      // 2 x nblk: per block (#sure, #equal-to-threshold)
-  uint32_t* blk_off;      // 2 x nblk: per block (output offset, #equal before)
   int32_t nblk_cap;
   int32_t* err_flag;      // device: nonzero once a bad label / index was seen
   uint32_t* host_pin;     // pinned host words for read-backs

@@ -55,14 +55,10 @@ __device__ __forceinline__ uint32_t pos_nibble(const uint32_t* __restrict__ pos_
   return (pos_bits[q >> 3] >> ((q & 7u) * 4u)) & 0xFu;
 }
 
-__global__ void sample_init_kernel(uint32_t* __restrict__ pos_bits, int64_t nwords,
-                                   uint32_t* __restrict__ hist, SelState* __restrict__ sel) {
-  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = t; i < nwords; i += stride) pos_bits[i] = 0u;
-  for (int64_t i = t; i < 3 * kHistStride; i += stride) hist[i] = 0u;
-  if (t < (int64_t)(sizeof(SelState) / 4)) reinterpret_cast<uint32_t*>(sel)[t] = 0u;
-}
+// Between two calls the sampler's scratch is all zero (bitmap, histograms, counter of positives):
+// pfc_create clears it once, and the last reader of each piece clears it again -- the scan of a
+// pass its histogram, the first scan the counter, the label remap the bitmap words it knows to be
+// set -- so no call starts with a clearing pass.
 
 __global__ void sample_mark_kernel(const int64_t* __restrict__ labels, int B, int64_t N,
                                    uint32_t* __restrict__ pos_bits, int32_t* __restrict__ err_flag) {
@@ -127,7 +123,7 @@ __global__ void sample_hist_kernel(int64_t N, PhiloxKey key, const uint32_t* __r
 // One block of 256 threads: walk the histogram from the largest bin downwards until `need`
 // classes are covered; fix the bin as the next bits of the threshold.
 template <int P>
-__global__ void sample_scan_kernel(const uint32_t* __restrict__ hist, SelState* __restrict__ sel,
+__global__ void sample_scan_kernel(uint32_t* __restrict__ hist, SelState* __restrict__ sel,
                                    uint32_t ceil_rN) {
   __shared__ uint32_t wsum[4];
   __shared__ uint32_t s_need, s_none;
@@ -136,9 +132,12 @@ __global__ void sample_scan_kernel(const uint32_t* __restrict__ hist, SelState* 
     if (P == 0) {
       const uint32_t U = sel->U;
       const uint32_t k = U > ceil_rN ? U : ceil_rN;
+      sel->U = 0u;        // last reader: ready for the next call
       sel->k = k;
+      sel->prefix = 0u;
       s_need = k - U;
       s_none = (k == U) ? 1u : 0u;
+      sel->need = s_need;
       sel->none = s_none;
     } else {
       s_need = sel->need;
@@ -146,14 +145,21 @@ __global__ void sample_scan_kernel(const uint32_t* __restrict__ hist, SelState* 
     }
   }
   __syncthreads();
-  if (s_none) return;
-  const uint32_t need = s_need;
   constexpr int kBins = Pass<P>::kBins;
   constexpr int kPer = kBins / 256;
-  // thread t owns the descending bins kBins-1-t*kPer .. kBins-1-(t*kPer+kPer-1)
+  // thread t owns the descending bins kBins-1-t*kPer .. kBins-1-(t*kPer+kPer-1); it is their last
+  // reader and leaves them cleared
+  uint32_t own[kPer];
   uint32_t mine = 0;
 #pragma unroll
-  for (int e = 0; e < kPer; ++e) mine += hist[P * kHistStride + (kBins - 1 - (t * kPer + e))];
+  for (int e = 0; e < kPer; ++e) {
+    uint32_t* h = &hist[P * kHistStride + (kBins - 1 - (t * kPer + e))];
+    own[e] = *h;
+    *h = 0u;
+    mine += own[e];
+  }
+  if (s_none) return;
+  const uint32_t need = s_need;
   // inclusive scan over threads
   uint32_t inc = mine;
   const int lane = t & 63, w = t >> 6;
@@ -170,9 +176,10 @@ __global__ void sample_scan_kernel(const uint32_t* __restrict__ hist, SelState* 
   const uint32_t exc = inc - mine;
   if (exc < need && need <= inc) {
     uint32_t cum = exc;
+#pragma unroll
     for (int e = 0; e < kPer; ++e) {
       const int b = kBins - 1 - (t * kPer + e);
-      const uint32_t c = hist[P * kHistStride + b];
+      const uint32_t c = own[e];
       if (cum + c >= need) {
         sel->need = need - cum;   // how many to take from inside this bin
         sel->prefix = sel->prefix | ((uint32_t)b << Pass<P>::kShift);
@@ -257,44 +264,26 @@ __global__ void sample_count_kernel(int64_t N, PhiloxKey key, const uint32_t* __
   }
 }
 
-// One block: turn per-block counts into per-block output offsets.  A block takes its
-// equal-to-threshold classes only while the quota sel->need lasts (smaller ids first).
-__global__ void sample_blkscan_kernel(int nblk, const uint32_t* __restrict__ blk_cnt,
-                                      uint32_t* __restrict__ blk_off, SelState* __restrict__ sel) {
-  __shared__ uint32_t sm[4];
-  const uint32_t need_eq = sel->none ? 0u : sel->need;
-  uint32_t run_eq = 0, run_sel = 0;
-  for (int b0 = 0; b0 < nblk; b0 += kThreads) {
-    const int b = b0 + threadIdx.x;
-    const uint32_t cs = b < nblk ? blk_cnt[2 * b] : 0u;
-    const uint32_t ce = b < nblk ? blk_cnt[2 * b + 1] : 0u;
-    uint32_t tot_e, tot_s;
-    const uint32_t eq_before = run_eq + block_excl_scan(ce, sm, tot_e);
-    uint32_t take = 0;
-    if (eq_before < need_eq) {
-      take = need_eq - eq_before;
-      if (take > ce) take = ce;
-    }
-    const uint32_t off = run_sel + block_excl_scan(cs + take, sm, tot_s);
-    if (b < nblk) {
-      blk_off[2 * b] = off;
-      blk_off[2 * b + 1] = eq_before;
-    }
-    run_eq += tot_e;
-    run_sel += tot_s;
-  }
-  if (threadIdx.x == 0) sel->total = run_sel;
-}
-
+// Ordered write of S.  Every block first adds up the counts of the blocks in front of it: its
+// output offset is their "sure" classes plus the equal-to-threshold ones they were allowed to
+// keep -- the quota sel->need is used up in ascending class id, so that is min(quota, number of
+// equal classes in front).  The last block also leaves the total in sel->total.
 __global__ void sample_write_kernel(int64_t N, PhiloxKey key, const uint32_t* __restrict__ pos_bits,
-                                    const SelState* __restrict__ sel,
-                                    const uint32_t* __restrict__ blk_off, int64_t cap,
+                                    SelState* __restrict__ sel,
+                                    const uint32_t* __restrict__ blk_cnt, int64_t cap,
                                     int32_t* __restrict__ idx_out) {
   __shared__ uint32_t sm[4];
   const uint32_t T = sel->prefix, none = sel->none;
   const uint32_t need_eq = none ? 0u : sel->need;
-  uint32_t out = blk_off[2 * blockIdx.x];
-  uint32_t eq_run = blk_off[2 * blockIdx.x + 1];
+  uint32_t front_sure = 0, front_eq = 0;
+  for (uint32_t b = threadIdx.x; b < blockIdx.x; b += kThreads) {
+    front_sure += blk_cnt[2 * b];
+    front_eq += blk_cnt[2 * b + 1];
+  }
+  front_sure = block_sum(front_sure, sm);
+  front_eq = block_sum(front_eq, sm);
+  uint32_t out = front_sure + (front_eq < need_eq ? front_eq : need_eq);
+  uint32_t eq_run = front_eq;
 #pragma unroll
   for (int it = 0; it < kItersPerBlock; ++it) {
     const uint32_t q = blockIdx.x * (kClassesPerBlock / 4) + it * kThreads + threadIdx.x;
@@ -322,12 +311,14 @@ __global__ void sample_write_kernel(int64_t N, PhiloxKey key, const uint32_t* __
     eq_run += tot_e;
     out += tot_s;
   }
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) sel->total = out;
 }
 
 // labels_local[i] = position of labels[i] in the ascending idx (binary search), -1 if absent.
 __global__ void sample_remap_kernel(const int64_t* __restrict__ labels, int B, int64_t N,
                                     const int32_t* __restrict__ idx, const SelState* __restrict__ sel,
-                                    int64_t cap, int32_t* __restrict__ yl_out) {
+                                    int64_t cap, int32_t* __restrict__ yl_out,
+                                    uint32_t* __restrict__ pos_bits) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B) return;
   const int64_t y = labels[i];
@@ -343,6 +334,8 @@ __global__ void sample_remap_kernel(const int64_t* __restrict__ labels, int B, i
     if (lo < k && idx[lo] == (int32_t)y) res = (int32_t)lo;
   }
   yl_out[i] = res;
+  // last user of the "is in the batch" bits: clear this label's word for the next call
+  if (y >= 0 && y < N) pos_bits[y >> 5] = 0u;
 }
 
 }  // namespace
@@ -362,19 +355,13 @@ int sample_impl(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t
   key.c3 = (uint32_t)(step >> 32);
   key.mask = score_mask;
 
-  const int64_t nwords = (N + 31) / 32 + 1;
   const int nblk = (int)((N + kClassesPerBlock - 1) / kClassesPerBlock);
   if (nblk > c->nblk_cap) return PFC_EINVAL;
   const int64_t nq = (N + 3) / 4;
   int hist_blocks = (int)((nq + kThreads * 4 - 1) / (kThreads * 4));
   if (hist_blocks > 512) hist_blocks = 512;
   if (hist_blocks < 1) hist_blocks = 1;
-  int init_blocks = (int)((nwords + kThreads - 1) / kThreads);
-  if (init_blocks > 1024) init_blocks = 1024;
-  if (init_blocks < 48) init_blocks = 48;   // also covers the 3 x 4096 histogram words
 
-  PFC_LAUNCH(c, KID_SAMPLE_INIT, sample_init_kernel, dim3(init_blocks), dim3(kThreads), 0,
-             c->pos_bits, nwords, c->hist, c->sel);
   PFC_LAUNCH(c, KID_SAMPLE_MARK, sample_mark_kernel, dim3((B + kThreads - 1) / kThreads),
              dim3(kThreads), 0, labels, B, N, c->pos_bits, c->err_flag);
   PFC_LAUNCH(c, KID_SAMPLE_HIST0, sample_hist_kernel<0>, dim3(hist_blocks), dim3(kThreads), 0, N,
@@ -391,12 +378,10 @@ int sample_impl(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t
              c->sel, (uint32_t)crn);
   PFC_LAUNCH(c, KID_SAMPLE_COUNT, sample_count_kernel, dim3(nblk), dim3(kThreads), 0, N, key,
              c->pos_bits, c->sel, c->blk_cnt);
-  PFC_LAUNCH(c, KID_SAMPLE_BLKSCAN, sample_blkscan_kernel, dim3(1), dim3(kThreads), 0, nblk,
-             c->blk_cnt, c->blk_off, c->sel);
   PFC_LAUNCH(c, KID_SAMPLE_WRITE, sample_write_kernel, dim3(nblk), dim3(kThreads), 0, N, key,
-             c->pos_bits, c->sel, c->blk_off, cap, idx_out);
+             c->pos_bits, c->sel, c->blk_cnt, cap, idx_out);
   PFC_LAUNCH(c, KID_SAMPLE_REMAP, sample_remap_kernel, dim3((B + kThreads - 1) / kThreads),
-             dim3(kThreads), 0, labels, B, N, idx_out, c->sel, cap, yl_out);
+             dim3(kThreads), 0, labels, B, N, idx_out, c->sel, cap, yl_out, c->pos_bits);
 
   if (crn >= (int64_t)B) {
     // U <= B <= ceil(r*N): k is known without the labels.
