@@ -16,8 +16,7 @@ void set_hip_error(hipError_t e, const char* what) {
 }
 
 static const char* const kKernelNames[KID_COUNT] = {
-    "sample_mark",  "sample_hist0", "sample_scan0", "sample_hist1",
-    "sample_scan1",  "sample_hist2", "sample_scan2", "sample_count",
+    "sample_mark",  "sample_hist0", "sample_hist1", "sample_hist2", "sample_count",
     "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_logits",
     "row_combine",   "gemm_dweight", "dweight_reduce", "dweight_label",
     "gemm_dfeatures", "dfeatures_final", "update", "gemm_dweight_update"};

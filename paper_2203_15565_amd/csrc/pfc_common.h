@@ -22,11 +22,8 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 enum KernelId {
   KID_SAMPLE_MARK = 0,
   KID_SAMPLE_HIST0,
-  KID_SAMPLE_SCAN0,
   KID_SAMPLE_HIST1,
-  KID_SAMPLE_SCAN1,
   KID_SAMPLE_HIST2,
-  KID_SAMPLE_SCAN2,
   KID_SAMPLE_COUNT,
   KID_SAMPLE_WRITE,
   KID_SAMPLE_REMAP,
@@ -46,12 +43,12 @@ enum KernelId {
 
 // State of the radix select, kept in device memory between the sampler's kernels.
 struct SelState {
-  uint32_t U;        // number of distinct labels (positives)
-  uint32_t k;        // |S| = max(U, ceil(r*N))
-  uint32_t need;     // negatives still to be taken inside the current prefix bin
-  uint32_t prefix;   // threshold bits fixed so far (in place, low bits zero)
-  uint32_t none;     // 1: no negative is taken at all (k == U)
-  uint32_t total;    // number of ids written (must equal k)
+  uint32_t U;          // number of distinct labels (positives); cleared again once consumed
+  uint32_t k;          // |S| = max(U, ceil(r*N))
+  uint32_t none;       // 1: no negative is taken at all (k == U)
+  uint32_t total;      // number of ids written (must equal k)
+  uint32_t need[3];    // after radix pass P: negatives still to be taken inside the chosen bin
+  uint32_t prefix[3];  // after radix pass P: threshold bits fixed so far (in place, low bits zero)
   uint32_t pad[2];
 };
 

@@ -72,22 +72,118 @@ __global__ void sample_mark_kernel(const int64_t* __restrict__ labels, int B, in
   atomicOr(&pos_bits[y >> 5], 1u << (y & 31));
 }
 
+// All 256 threads of a workgroup: walk the merged histogram of pass P from the largest bin
+// downwards until `need` classes are covered.  Returns (to every thread) the bin that holds the
+// threshold and how many classes are still to be taken from inside it.  Every workgroup of the
+// launch that follows pass P does this for itself -- the same integers everywhere -- instead of a
+// one-workgroup launch in between.
+template <int P>
+__device__ __forceinline__ void find_bin(const uint32_t* __restrict__ hist, uint32_t need,
+                                         uint32_t& bin, uint32_t& need_inside) {
+  __shared__ uint32_t wsum[4];
+  __shared__ uint32_t s_bin, s_need;
+  constexpr int kBins = Pass<P>::kBins;
+  constexpr int kPer = kBins / kThreads;
+  const int t = threadIdx.x;
+  // thread t owns the descending bins kBins-1-t*kPer .. kBins-1-(t*kPer+kPer-1)
+  uint32_t own[kPer];
+  uint32_t mine = 0;
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) {
+    own[e] = hist[P * kHistStride + (kBins - 1 - (t * kPer + e))];
+    mine += own[e];
+  }
+  uint32_t inc = mine;   // inclusive scan over threads
+  const int lane = t & 63, w = t >> 6;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t n = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += n;
+  }
+  if (lane == 63) wsum[w] = inc;
+  if (t == 0) {
+    s_bin = 0u;
+    s_need = 0u;
+  }
+  __syncthreads();
+  uint32_t base = 0;
+  for (int i = 0; i < w; ++i) base += wsum[i];
+  inc += base;
+  const uint32_t exc = inc - mine;
+  if (exc < need && need <= inc) {   // true in exactly one thread (if need >= 1)
+    uint32_t cum = exc;
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+      if (cum + own[e] >= need) {
+        s_bin = (uint32_t)(kBins - 1 - (t * kPer + e));
+        s_need = need - cum;
+        break;
+      }
+      cum += own[e];
+    }
+  }
+  __syncthreads();
+  bin = s_bin;
+  need_inside = s_need;
+  __syncthreads();
+}
+
+// State of the select after pass P-1, found by every workgroup of the launch of pass P (or of the
+// count launch, P = 3) from the histogram of pass P-1 and what workgroup 0 of the launch before
+// left in `sel`.  Workgroup 0 records the new state for the next launch and clears what nobody
+// reads any more (the histogram of pass P-2, the count of positives).
+template <int P>
+__device__ __forceinline__ void select_state(uint32_t* __restrict__ hist, SelState* __restrict__ sel,
+                                             uint32_t ceil_rN, uint32_t& prefix, uint32_t& need,
+                                             uint32_t& none) {
+  static_assert(P >= 1 && P <= 3, "state after pass P-1");
+  uint32_t need_in, prefix_in;
+  if constexpr (P == 1) {
+    const uint32_t U = sel->U;
+    const uint32_t k = U > ceil_rN ? U : ceil_rN;
+    none = (k == U) ? 1u : 0u;
+    need_in = k - U;
+    prefix_in = 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      sel->k = k;
+      sel->none = none;
+    }
+  } else {
+    none = sel->none;
+    need_in = sel->need[P - 2];
+    prefix_in = sel->prefix[P - 2];
+  }
+  uint32_t bin = 0u;
+  need = 0u;
+  if (!none) find_bin<P - 1>(hist, need_in, bin, need);
+  prefix = prefix_in | (bin << Pass<P - 1>::kShift);
+  if (blockIdx.x == 0) {
+    if (threadIdx.x == 0) {
+      sel->need[P - 1] = need;
+      sel->prefix[P - 1] = prefix;
+      if (P == 2) sel->U = 0u;
+    }
+    if constexpr (P >= 2) {
+      constexpr int kOld = Pass<P - 2>::kBins;
+      for (int b = threadIdx.x; b < kOld; b += kThreads) hist[(P - 2) * kHistStride + b] = 0u;
+    }
+  }
+}
+
 // Radix pass P over the non-positive classes whose score agrees with the prefix found so far;
 // pass 0 also counts the positives.
 template <int P>
 __global__ void sample_hist_kernel(int64_t N, PhiloxKey key, const uint32_t* __restrict__ pos_bits,
-                                   uint32_t* __restrict__ hist, SelState* __restrict__ sel) {
+                                   uint32_t* __restrict__ hist, SelState* __restrict__ sel,
+                                   uint32_t ceil_rN) {
   constexpr int kBins = Pass<P>::kBins, kShift = Pass<P>::kShift;
   __shared__ uint32_t lh[kBins];
   __shared__ uint32_t lpos;
   for (int b = threadIdx.x; b < kBins; b += blockDim.x) lh[b] = 0u;
   if (threadIdx.x == 0) lpos = 0u;
+  uint32_t prefix = 0u, need = 0u, none = 0u;
+  if constexpr (P > 0) select_state<P>(hist, sel, ceil_rN, prefix, need, none);
   __syncthreads();
-  uint32_t prefix = 0u, none = 0u;
-  if (P > 0) {
-    prefix = sel->prefix;
-    none = sel->none;
-  }
   if (!(P > 0 && none)) {
     const uint32_t nq = (uint32_t)((N + 3) >> 2);
     uint32_t npos = 0;
@@ -118,76 +214,6 @@ __global__ void sample_hist_kernel(int64_t N, PhiloxKey key, const uint32_t* __r
     if (c) atomicAdd(&hist[P * kHistStride + b], c);
   }
   if (P == 0 && threadIdx.x == 0 && lpos) atomicAdd(&sel->U, lpos);
-}
-
-// One block of 256 threads: walk the histogram from the largest bin downwards until `need`
-// classes are covered; fix the bin as the next bits of the threshold.
-template <int P>
-__global__ void sample_scan_kernel(uint32_t* __restrict__ hist, SelState* __restrict__ sel,
-                                   uint32_t ceil_rN) {
-  __shared__ uint32_t wsum[4];
-  __shared__ uint32_t s_need, s_none;
-  const int t = threadIdx.x;
-  if (t == 0) {
-    if (P == 0) {
-      const uint32_t U = sel->U;
-      const uint32_t k = U > ceil_rN ? U : ceil_rN;
-      sel->U = 0u;        // last reader: ready for the next call
-      sel->k = k;
-      sel->prefix = 0u;
-      s_need = k - U;
-      s_none = (k == U) ? 1u : 0u;
-      sel->need = s_need;
-      sel->none = s_none;
-    } else {
-      s_need = sel->need;
-      s_none = sel->none;
-    }
-  }
-  __syncthreads();
-  constexpr int kBins = Pass<P>::kBins;
-  constexpr int kPer = kBins / 256;
-  // thread t owns the descending bins kBins-1-t*kPer .. kBins-1-(t*kPer+kPer-1); it is their last
-  // reader and leaves them cleared
-  uint32_t own[kPer];
-  uint32_t mine = 0;
-#pragma unroll
-  for (int e = 0; e < kPer; ++e) {
-    uint32_t* h = &hist[P * kHistStride + (kBins - 1 - (t * kPer + e))];
-    own[e] = *h;
-    *h = 0u;
-    mine += own[e];
-  }
-  if (s_none) return;
-  const uint32_t need = s_need;
-  // inclusive scan over threads
-  uint32_t inc = mine;
-  const int lane = t & 63, w = t >> 6;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t n = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += n;
-  }
-  if (lane == 63) wsum[w] = inc;
-  __syncthreads();
-  uint32_t base = 0;
-  for (int i = 0; i < w; ++i) base += wsum[i];
-  inc += base;
-  const uint32_t exc = inc - mine;
-  if (exc < need && need <= inc) {
-    uint32_t cum = exc;
-#pragma unroll
-    for (int e = 0; e < kPer; ++e) {
-      const int b = kBins - 1 - (t * kPer + e);
-      const uint32_t c = own[e];
-      if (cum + c >= need) {
-        sel->need = need - cum;   // how many to take from inside this bin
-        sel->prefix = sel->prefix | ((uint32_t)b << Pass<P>::kShift);
-        break;
-      }
-      cum += c;
-    }
-  }
 }
 
 // Selection predicate pieces for classes 4q..4q+3: bit e of `sure` = positive or score above the
@@ -244,9 +270,11 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, ui
 }
 
 __global__ void sample_count_kernel(int64_t N, PhiloxKey key, const uint32_t* __restrict__ pos_bits,
-                                    const SelState* __restrict__ sel, uint32_t* __restrict__ blk_cnt) {
+                                    uint32_t* __restrict__ hist, SelState* __restrict__ sel,
+                                    uint32_t ceil_rN, uint32_t* __restrict__ blk_cnt) {
   __shared__ uint32_t sm[4];
-  const uint32_t T = sel->prefix, none = sel->none;
+  uint32_t T, need, none;
+  select_state<3>(hist, sel, ceil_rN, T, need, none);   // the full 32-bit threshold
   uint32_t nsure = 0, neq = 0;
 #pragma unroll
   for (int it = 0; it < kItersPerBlock; ++it) {
@@ -269,12 +297,14 @@ __global__ void sample_count_kernel(int64_t N, PhiloxKey key, const uint32_t* __
 // keep -- the quota sel->need is used up in ascending class id, so that is min(quota, number of
 // equal classes in front).  The last block also leaves the total in sel->total.
 __global__ void sample_write_kernel(int64_t N, PhiloxKey key, const uint32_t* __restrict__ pos_bits,
-                                    SelState* __restrict__ sel,
+                                    SelState* __restrict__ sel, uint32_t* __restrict__ hist,
                                     const uint32_t* __restrict__ blk_cnt, int64_t cap,
                                     int32_t* __restrict__ idx_out) {
   __shared__ uint32_t sm[4];
-  const uint32_t T = sel->prefix, none = sel->none;
-  const uint32_t need_eq = none ? 0u : sel->need;
+  const uint32_t T = sel->prefix[2], none = sel->none;
+  const uint32_t need_eq = none ? 0u : sel->need[2];
+  if (blockIdx.x == 0)   // nobody reads the last pass's histogram any more
+    for (int b = threadIdx.x; b < Pass<2>::kBins; b += kThreads) hist[2 * kHistStride + b] = 0u;
   uint32_t front_sure = 0, front_eq = 0;
   for (uint32_t b = threadIdx.x; b < blockIdx.x; b += kThreads) {
     front_sure += blk_cnt[2 * b];
@@ -365,21 +395,15 @@ int sample_impl(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t
   PFC_LAUNCH(c, KID_SAMPLE_MARK, sample_mark_kernel, dim3((B + kThreads - 1) / kThreads),
              dim3(kThreads), 0, labels, B, N, c->pos_bits, c->err_flag);
   PFC_LAUNCH(c, KID_SAMPLE_HIST0, sample_hist_kernel<0>, dim3(hist_blocks), dim3(kThreads), 0, N,
-             key, c->pos_bits, c->hist, c->sel);
-  PFC_LAUNCH(c, KID_SAMPLE_SCAN0, sample_scan_kernel<0>, dim3(1), dim3(kThreads), 0, c->hist,
-             c->sel, (uint32_t)crn);
+             key, c->pos_bits, c->hist, c->sel, (uint32_t)crn);
   PFC_LAUNCH(c, KID_SAMPLE_HIST1, sample_hist_kernel<1>, dim3(hist_blocks), dim3(kThreads), 0, N,
-             key, c->pos_bits, c->hist, c->sel);
-  PFC_LAUNCH(c, KID_SAMPLE_SCAN1, sample_scan_kernel<1>, dim3(1), dim3(kThreads), 0, c->hist,
-             c->sel, (uint32_t)crn);
+             key, c->pos_bits, c->hist, c->sel, (uint32_t)crn);
   PFC_LAUNCH(c, KID_SAMPLE_HIST2, sample_hist_kernel<2>, dim3(hist_blocks), dim3(kThreads), 0, N,
-             key, c->pos_bits, c->hist, c->sel);
-  PFC_LAUNCH(c, KID_SAMPLE_SCAN2, sample_scan_kernel<2>, dim3(1), dim3(kThreads), 0, c->hist,
-             c->sel, (uint32_t)crn);
+             key, c->pos_bits, c->hist, c->sel, (uint32_t)crn);
   PFC_LAUNCH(c, KID_SAMPLE_COUNT, sample_count_kernel, dim3(nblk), dim3(kThreads), 0, N, key,
-             c->pos_bits, c->sel, c->blk_cnt);
+             c->pos_bits, c->hist, c->sel, (uint32_t)crn, c->blk_cnt);
   PFC_LAUNCH(c, KID_SAMPLE_WRITE, sample_write_kernel, dim3(nblk), dim3(kThreads), 0, N, key,
-             c->pos_bits, c->sel, c->blk_cnt, cap, idx_out);
+             c->pos_bits, c->sel, c->hist, c->blk_cnt, cap, idx_out);
   PFC_LAUNCH(c, KID_SAMPLE_REMAP, sample_remap_kernel, dim3((B + kThreads - 1) / kThreads),
              dim3(kThreads), 0, labels, B, N, idx_out, c->sel, cap, yl_out, c->pos_bits);
 
