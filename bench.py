@@ -213,6 +213,24 @@ def main() -> int:
         "mfma_bf16_TFLOPps": round(ctx.pfc_probe_mfma_bf16(5), 1),
     }
     del scratch
+    # the vendor GEMM on its best shape (square 8192^3, bf16), as a second yardstick for the MFMA side
+    try:
+        n = 8192
+        A = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
+        Bm = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
+        C = torch.empty(n, n, device=dev, dtype=torch.bfloat16)
+        for _ in range(3):
+            torch.matmul(A, Bm, out=C)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            torch.matmul(A, Bm, out=C)
+        e1.record()
+        torch.cuda.synchronize()
+        measured["vendor_gemm_8192_bf16_TFLOPps"] = round(2.0 * n ** 3 * 10 / e0.elapsed_time(e1) / 1e9, 1)
+        del A, Bm, C
+    except Exception:   # the yardstick is optional
+        measured["vendor_gemm_8192_bf16_TFLOPps"] = None
     ref = measured["stream_copy_GBps"] if roofline["bound"] == "hbm" else measured["mfma_bf16_TFLOPps"]
     roofline["frac_of_measured_peak"] = round(roofline["achieved"] / ref, 4)
 
