@@ -200,6 +200,14 @@ def main() -> int:
                 ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                            frac=round(ach / PEAK_HBM_GBS, 4))
         kernels[name] = ent
+    # the sampler: integer work only (five sweeps of one Philox4x32-10 block per four classes, about
+    # 70 integer operations each), so its yardstick is the integer ALU rate, 256 CUs x 64 lanes x
+    # 2.4 GHz = 39.3 Tops/s; in practice it is bound by its seven dependent launches
+    samp_ms = sum(ms for n, ms in kern_ms.items() if n.startswith("sample_"))
+    samp_ops = 5.0 * (wl.N / 4.0) * 70.0
+    sampler = {"ms": round(samp_ms, 5), "launches": sum(1 for n in kern_ms if n.startswith("sample_")),
+               "bound": "alu", "achieved": round(samp_ops / (samp_ms * 1e-3) / 1e12, 3), "peak": 39.3,
+               "unit": "Tops/s", "frac": round(samp_ops / (samp_ms * 1e-3) / 1e12 / 39.3, 4)}
     dominant = max((n for n in kern_ms if n in work), key=lambda n: kern_ms[n])
     roofline = {"kernel": dominant}
     roofline.update({f: kernels[dominant][f] for f in ("bound", "achieved", "peak", "unit", "frac")})
@@ -264,6 +272,7 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "measured_peaks": measured,
+        "sampler": sampler,
         "kernels": kernels,
         "kernel_sum_ms": round(sum(kern_ms.values()), 4),
         "final_loss": float(loss.item()),
