@@ -2,10 +2,14 @@
 """Benchmark of one Partial FC training step (sample + forward/backward + update) on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline] [--no-cpu-baseline]
+                    [--fused]
 
 Prints ONE JSON line: whole-step throughput in samples/s with all inputs resident in HBM, the
 roofline of the dominant kernel (measured with HIP events on the library's stream) and the fp64
-CPU oracle timed on the same workload as a reported baseline.
+CPU oracle timed on the same workload as a reported baseline.  `value` is the sequence the metric
+names, pfc_sample + pfc_forward_backward + pfc_update; the sequence with the one fused call
+pfc_forward_backward_update is timed as well and reported as `value_fused_call` (--fused swaps
+the two).  `calls_ms` holds the duration of every ABI call on its own.
 """
 from __future__ import annotations
 
@@ -62,9 +66,12 @@ def main() -> int:
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--r", type=float, default=None, help="override the sampling ratio")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--two-calls", action="store_true",
-                    help="pfc_forward_backward + pfc_update instead of the one fused call")
+    ap.add_argument("--fused", action="store_true",
+                    help="make `value` the pfc_sample + pfc_forward_backward_update sequence (one "
+                         "call for forward/backward and update) instead of the three calls the "
+                         "metric names; both sequences are timed and reported either way")
     args = ap.parse_args()
+    args.two_calls = not args.fused
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -174,21 +181,55 @@ def main() -> int:
     torch.cuda.synchronize()
     other_elapsed = time.perf_counter() - t0
 
-    # ---- per-kernel durations: same steps again with an event pair around every kernel ----
-    ctx.pfc_set_timing(True)
-    acc: dict = {}
+    # ---- per-call durations: an event pair around every ABI call (the library's stream is torch's
+    # current stream, so torch events see it), averaged over the same steps ----
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        r = fn()
+        e1.record()
+        return r, (e0, e1)
+
+    call_ev: dict = {}
     reps = min(K, 10)
     for t in range(reps):
-        step(Wm + t)
-        for name, ms in ctx.pfc_get_timing().items():
-            acc.setdefault(name, []).append(ms)
+        tt = Wm + t
+        kk, ev = timed(lambda: ctx.pfc_sample(labels[tt], wl.r, wl.seed, tt, idx, yl))
+        call_ev.setdefault("pfc_sample", []).append(ev)
+        _, ev = timed(lambda: ctx.pfc_forward_backward(feats[tt], Wd, idx, kk, yl, wl.s, wl.m, loss,
+                                                       dX, dW))
+        call_ev.setdefault("pfc_forward_backward", []).append(ev)
+        _, ev = timed(lambda: ctx.pfc_update(Wd, vd, idx, kk, dW, wl.lr, wl.mu))
+        call_ev.setdefault("pfc_update", []).append(ev)
+        ctx.pfc_sample(labels[tt], wl.r, wl.seed, tt, idx, yl)
+        _, ev = timed(lambda: ctx.pfc_forward_backward_update(feats[tt], Wd, vd, idx, kk, yl, wl.s,
+                                                              wl.m, wl.lr, wl.mu, loss, dX))
+        call_ev.setdefault("pfc_forward_backward_update", []).append(ev)
+    torch.cuda.synchronize()
+    calls_ms = {n: round(float(np.mean([a.elapsed_time(b) for a, b in evs])), 5)
+                for n, evs in call_ev.items()}
+
+    # ---- per-kernel durations: same steps again with an event pair around every kernel, for both
+    # call sequences (the timed one last, so that a kernel both use is reported from it) ----
+    ctx.pfc_set_timing(True)
+    acc: dict = {}
+    acc_other: dict = {}
+    for which, dst in ((other, acc_other), (args.two_calls, acc)):
+        for t in range(reps):
+            step(Wm + t, which)
+            for name, ms in ctx.pfc_get_timing().items():
+                dst.setdefault(name, []).append(ms)
+        ctx.pfc_set_timing(True)     # forget the launches of this sequence
     ctx.pfc_set_timing(False)
     kern_ms = {n: float(np.mean(v)) for n, v in acc.items()}
+    other_only_ms = {n: float(np.mean(v)) for n, v in acc_other.items() if n not in kern_ms}
     work = algorithmic_work(wl.B, wl.D, k, wl.precision)
     peak_mfma = PEAK_BF16_TFLOPS if wl.precision == 1 else PEAK_FP32_MFMA_TFLOPS
     kernels = {}
-    for name, ms in sorted(kern_ms.items(), key=lambda kv: -kv[1]):
+    for name, ms in sorted(list(kern_ms.items()) + list(other_only_ms.items()), key=lambda kv: -kv[1]):
         ent = {"ms": round(ms, 5)}
+        if name in other_only_ms:
+            ent["sequence"] = "other"      # launched only by the call sequence that is not `value`
         if name in work:
             bound, amount = work[name]
             if bound == "mfma":
@@ -261,6 +302,10 @@ def main() -> int:
                    "B": wl.B, "D": wl.D, "N": wl.N, "r": wl.r, "k": k,
                    "calls": "pfc_sample + pfc_forward_backward + pfc_update" if args.two_calls
                    else "pfc_sample + pfc_forward_backward_update"},
+        # both sequences side by side, whichever one `value` is
+        "value_three_calls": round(value if args.two_calls else wl.B * K / other_elapsed, 1),
+        "value_fused_call": round(wl.B * K / other_elapsed if args.two_calls else value, 1),
+        "calls_ms": calls_ms,
         "other_call_sequence": {
             "calls": "pfc_sample + pfc_forward_backward + pfc_update" if other
             else "pfc_sample + pfc_forward_backward_update",

@@ -109,6 +109,12 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   c->kp_cap = round_up(c->k_cap, kPadK);
   c->Bp_cap = (int32_t)round_up(B_max, kPadB);
   c->esize = precision == PFC_PRECISION_BF16 ? 2 : 4;
+  // the GEMM staging code addresses up to 64 rows of E (row length kp elements) through one
+  // 32-bit byte offset per thread
+  if ((uint64_t)c->kp_cap * 64u * c->esize >= ((uint64_t)1 << 32)) {
+    delete c;
+    return PFC_EINVAL;
+  }
 
   const size_t es = c->esize;
   const size_t Bp = (size_t)c->Bp_cap, kp = (size_t)c->kp_cap, Dz = (size_t)D;

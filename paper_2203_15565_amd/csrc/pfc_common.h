@@ -97,6 +97,7 @@ struct pfc_ctx {
 
   // timing
   int32_t num_cu;   // compute units of the device
+  int32_t lds_attr_set;   // the dynamic LDS limit of the GEMM kernels has been raised
   int32_t timing;
   hipEvent_t ev0[pfc::KID_COUNT];
   hipEvent_t ev1[pfc::KID_COUNT];

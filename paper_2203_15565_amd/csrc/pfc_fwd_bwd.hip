@@ -360,7 +360,7 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
     float l = 0.f;
     for (int t = lane; t < tiles_j; t += 64) l += rowpart[(int64_t)i * tiles_j + t];
     l = wave_sum(l);
-    scale = lp.s / ((float)B * l);
+    scale = (lp.s / (float)B) / l;   // B * l could leave the fp32 range, s/B never does
     float mx = -2.f;
     if (lp.extras) {
       for (int t = lane; t < tiles_j; t += 64) mx = fmaxf(mx, rowmaxpart[(int64_t)i * tiles_j + t]);
@@ -614,11 +614,16 @@ __device__ __forceinline__ void fused_update_tile(
   f32x4 w[WIN][NC], v[WIN][NC];
   auto request = [&](int n) {
     const int64_t row = __builtin_amdgcn_readlane(idxv, n);   // wave-uniform
-    const int64_t off = (row >= 0 ? row : 0) * D + lane * 4;  // row 0 stands in for a missing row
+    const int64_t off = row * D + lane * 4;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      w[n % WIN][c] = *reinterpret_cast<const f32x4*>(W + off + c * 256);
-      v[n % WIN][c] = *reinterpret_cast<const f32x4*>(V + off + c * 256);
+      if (row >= 0) {   // padding or a bad id: nothing is read (and nothing written below)
+        w[n % WIN][c] = *reinterpret_cast<const f32x4*>(W + off + c * 256);
+        v[n % WIN][c] = *reinterpret_cast<const f32x4*>(V + off + c * 256);
+      } else {
+        w[n % WIN][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+        v[n % WIN][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
     }
   };
 #pragma unroll
@@ -895,8 +900,9 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   PFC_LAUNCH(c, KID_GATHER_W, gather_kernel, dim3((unsigned)((kp / 4 + 3) / 4)), dim3(256), 0, W,
              c->N, idx, k, kp, D, Wn, c->rnormW, c->head, c->err_flag);
 
-  static bool attr_done = false;   // per instantiation: raise the dynamic LDS limit once
-  if (!attr_done) {
+  // raise the dynamic LDS limit of this context's kernels once (a context has one precision and
+  // one D, hence one instantiation of run)
+  if (!c->lds_attr_set) {
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgF, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgF, true>,
@@ -909,7 +915,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgX::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)(gemm_dweight_update_kernel<CfgU, CfgUS>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLds));
-    attr_done = true;
+    c->lds_attr_set = 1;
   }
   {
     const int tiles_j = (int)(kp / CfgF::BM), tiles_i = Bp / CfgF::BN;
@@ -952,7 +958,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   auto launch_dfeatures = [&]() -> int {
     const int tiles_i = Bp / CfgX::BM, tiles_d = D / CfgX::BN;
     const int slabs_total = (int)(kp / CfgX::BK);
-    int want = 256 / (tiles_i * tiles_d);
+    int want = c->num_cu / (tiles_i * tiles_d);   // one workgroup per compute unit
     if (want < 1) want = 1;
     if (want > kMaxSplits) want = kMaxSplits;
     if (want > slabs_total) want = slabs_total;

@@ -4,7 +4,6 @@ from __future__ import annotations
 
 import numpy as np
 
-from oracle import pfc_oracle as O
 from paper_2203_15565_amd import binding
 
 
@@ -55,5 +54,32 @@ def row_rel_err(W_gpu, W_ref, ref_norm):
     return float((d / ref_norm).max())
 
 
-def oracle_step(X, labels, W64, v64, wl_kwargs):
-    return O.step(X, labels, W64, v64, **wl_kwargs)
+# Per-row gradient bars.  A center that is nobody's label has a gradient row whose largest entry
+# is only a few percent of the largest entry of the whole matrix (the label rows dominate), so a
+# bar relative to the global maximum says little about it; these bars are relative to each row's
+# own largest entry.  bf16 operands: every product carries two roundings of 2^-9 relative, the sum
+# over the batch adds them up like a random walk, so an entry is off by about 2^-9 of the row's
+# typical entry and the worst of D entries by 3-4 times that, below 1 % of the row's largest entry;
+# fp32 operands leave 1e-6.  Rows whose largest oracle entry is below ROW_FLOOR of the matrix's
+# largest entry are left to the global bar (nothing relative can be said about a row of zeros).
+ROW_GRAD_TOL = {binding.PRECISION_FP32: 1e-4, binding.PRECISION_BF16: 2e-2}
+ROW_FLOOR = 1e-6
+
+
+def row_rel_max(a, b, floor=ROW_FLOOR):
+    """max over rows of max|a_row - b_row| / max|b_row|, rows of b below floor * max|b| excluded.
+    Returns (worst ratio, number of rows compared)."""
+    a = np.asarray(a)
+    b = np.asarray(b)
+    worst, count = 0.0, 0
+    gmax = float(np.abs(b).max())
+    step = max(1, (1 << 24) // max(1, b.shape[1]))       # bounded fp64 temporaries
+    for r0 in range(0, b.shape[0], step):
+        bb = b[r0:r0 + step].astype(np.float64)
+        d = np.abs(a[r0:r0 + step].astype(np.float64) - bb).max(axis=1)
+        rmax = np.abs(bb).max(axis=1)
+        ok = rmax >= floor * gmax
+        if ok.any():
+            worst = max(worst, float((d[ok] / rmax[ok]).max()))
+            count += int(ok.sum())
+    return worst, count

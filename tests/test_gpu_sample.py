@@ -138,13 +138,13 @@ def test_sample_einval():
 def test_sample_full_size(name):
     """Bit-exact selection at the full class counts of the workloads (N up to 10M)."""
     wl = workloads.CONFIGS[name]
-    ctx = binding.Context(wl.N, wl.D, wl.B, wl.r, binding.PRECISION_BF16)
+    sweep = {"headline": (0.05, 0.2, 0.4), "large": (1.0,)}.get(name, ())
+    ctx = binding.Context(wl.N, 256, wl.B, max((wl.r,) + sweep), binding.PRECISION_BF16)
     for step in (0, 1):
         labels = workloads.make_labels(wl, step)
         _say("sample full size", name, step)
         _check(ctx, labels, wl.N, wl.r, wl.seed, step)
-    if name == "headline":
-        for r in (0.05, 0.1):
-            _say("sample headline r", r)
-            _check(ctx, workloads.make_labels(wl, 2), wl.N, r, wl.seed, 2)
+    for r in sweep:     # the other ratios of the headline sweep; full FC for the large workload
+        _say("sample", name, "r", r)
+        _check(ctx, workloads.make_labels(wl, 2), wl.N, r, wl.seed, 2)
     ctx.close()
