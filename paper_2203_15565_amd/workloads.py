@@ -8,6 +8,13 @@ fewer than 10 images).  The same arrays are handed to the HIP path and to the CP
 
 Everything is NumPy on the host (PCG64), so a given (config, step) is reproducible on any
 machine.  The large center matrices are generated in row chunks to bound host memory.
+
+Every stream of random numbers is seeded with the sequence (stream tag, config id, index): tag 1
+features (index = step), 2 labels (index = step), 3 initial centers (index = row chunk), 4 the
+class-id permutation.  The tags keep the streams apart whatever the ids are: NumPy pads a seed
+sequence with zeros, so plain integer seeds such as 1000*config + step and 3000 + config can name
+the same stream (config 3, step 3), which once made a batch of features an exact multiple of the
+first rows of the center matrix.
 """
 from __future__ import annotations
 
@@ -62,9 +69,12 @@ CONFIGS = {
 }
 
 
+_TAG_FEATURES, _TAG_LABELS, _TAG_WEIGHT, _TAG_PERM = 1, 2, 3, 4
+
+
 def make_features(wl: Workload, step: int) -> np.ndarray:
     """B x D i.i.d. N(0,1) fp32 features, fresh for every step."""
-    rng = np.random.default_rng(1000 * wl.cfg_id + step)
+    rng = np.random.default_rng([_TAG_FEATURES, wl.cfg_id, step])
     return rng.standard_normal((wl.B, wl.D), dtype=np.float32)
 
 
@@ -90,14 +100,14 @@ def _class_perm(wl: Workload) -> np.ndarray:
     key = (wl.cfg_id, wl.N)
     if key not in _perm_cache:
         _perm_cache.clear()
-        _perm_cache[key] = np.random.default_rng(4000 + wl.cfg_id).permutation(wl.N)
+        _perm_cache[key] = np.random.default_rng([_TAG_PERM, wl.cfg_id]).permutation(wl.N)
     return _perm_cache[key]
 
 
 def make_labels(wl: Workload, step: int) -> np.ndarray:
     """int64[B] labels: uniform over the classes, or long-tailed (Zipf over a seeded random
     permutation of the class ids, so that frequent classes are spread over the id range)."""
-    rng = np.random.default_rng(2000 * wl.cfg_id + step)
+    rng = np.random.default_rng([_TAG_LABELS, wl.cfg_id, step])
     if wl.label_dist == "uniform":
         return rng.integers(0, wl.N, size=wl.B, dtype=np.int64)
     if wl.label_dist == "zipf":
@@ -110,13 +120,12 @@ def make_labels(wl: Workload, step: int) -> np.ndarray:
 
 def weight_chunks(wl: Workload, rows_per_chunk: int = 1 << 18):
     """Yield (row0, chunk) of the initial center matrix: i.i.d. N(0, 0.01^2) fp32.
-    Chunk c is drawn from its own generator seeded by (3000 + cfg_id, c), so any chunk can
-    be regenerated alone."""
+    Chunk c is drawn from its own generator, so any chunk can be regenerated alone."""
     row0 = 0
     c = 0
     while row0 < wl.N:
         n = min(rows_per_chunk, wl.N - row0)
-        rng = np.random.default_rng([3000 + wl.cfg_id, c])
+        rng = np.random.default_rng([_TAG_WEIGHT, wl.cfg_id, c])
         chunk = rng.standard_normal((n, wl.D), dtype=np.float32)
         chunk *= np.float32(0.01)
         yield row0, chunk

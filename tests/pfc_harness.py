@@ -57,12 +57,15 @@ def row_rel_err(W_gpu, W_ref, ref_norm):
 # Per-row gradient bars.  A center that is nobody's label has a gradient row whose largest entry
 # is only a few percent of the largest entry of the whole matrix (the label rows dominate), so a
 # bar relative to the global maximum says little about it; these bars are relative to each row's
-# own largest entry.  bf16 operands: every product carries two roundings of 2^-9 relative, the sum
-# over the batch adds them up like a random walk, so an entry is off by about 2^-9 of the row's
-# typical entry and the worst of D entries by 3-4 times that, below 1 % of the row's largest entry;
-# fp32 operands leave 1e-6.  Rows whose largest oracle entry is below ROW_FLOOR of the matrix's
-# largest entry are left to the global bar (nothing relative can be said about a row of zeros).
-ROW_GRAD_TOL = {binding.PRECISION_FP32: 1e-4, binding.PRECISION_BF16: 2e-2}
+# own largest entry.  What sets them is the logit, not the sum over the batch: such a row is
+# often dominated by ONE sample, dWn_j ~ (s/B) p_ij xn_i, and p_ij = exp(s cos_ij)/l_i carries the
+# error of the cosine multiplied by s.  With bf16 operands every product xn_d wn_d is off by about
+# 2^-9 sqrt(2/3) relative, the sum over D = 512 terms of size 1/D by 7e-5, hence s |d cos| = 4.5e-3
+# rms at s = 64; the worst of the 4e7 .. 1e9 (sample, center) pairs of the workloads lies 5.5 to 6
+# standard deviations out: 2.5e-2 .. 3e-2 observed, bar 5e-2.  fp32 operands: s * 1e-7, bar 1e-4.
+# Rows whose largest oracle entry is below ROW_FLOOR of the matrix's largest entry are left to the
+# global bar (nothing relative can be said about a row of zeros).
+ROW_GRAD_TOL = {binding.PRECISION_FP32: 1e-4, binding.PRECISION_BF16: 5e-2}
 ROW_FLOOR = 1e-6
 
 

@@ -115,7 +115,7 @@ def test_fused_medium_workload_ten_steps():
 
 def test_fused_large_workload_ten_steps():
     # 36,024 sampled classes: the one-kernel form, with a last round of half-height tiles
-    _run_steps(workloads.CONFIGS["large"], 10, check_every_step=False, fused=True)
+    _run_steps(workloads.CONFIGS["large"], 10, fused=True)
 
 
 def test_fused_einval():

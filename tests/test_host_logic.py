@@ -58,6 +58,20 @@ def test_generators_are_reproducible_and_in_range():
     assert abs(float(X.mean())) < 0.02 and abs(float(X.std()) - 1.0) < 0.02
 
 
+def test_random_streams_of_the_generators_never_coincide():
+    """Features, labels, centers and the permutation draw from separate streams for every config
+    and step: no batch of features is a multiple of rows of the center matrix (which would make
+    cosines of exactly 1 and the projected center gradient a pure rounding residue)."""
+    heads = {}
+    for wl in workloads.CONFIGS.values():
+        small = wl.with_(B=2, N=min(wl.N, 64))
+        for row0, chunk in workloads.weight_chunks(small):
+            heads[("W", wl.name)] = tuple(np.round(chunk[0, :6] * 100, 4))
+        for t in range(12):
+            heads[("X", wl.name, t)] = tuple(np.round(workloads.make_features(small, t)[0, :6], 4))
+    assert len(set(heads.values())) == len(heads)
+
+
 def test_zipf_labels_are_long_tailed():
     wl = workloads.CONFIGS["large"]
     lab = np.concatenate([workloads.make_labels(wl, t) for t in range(20)])
