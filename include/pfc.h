@@ -83,6 +83,29 @@ int pfc_sample_masked(pfc_ctx* ctx, const int64_t* labels, int32_t B, double r,
                       int32_t* idx_out, int32_t* labels_local_out, int64_t* k_out);
 
 /*
+ * pfc_sample_noalloc -- pfc_sample for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  It needs no context: the
+ * sampler's scratch (bitmap of batch classes, radix histograms, block counts; 2.2 MB) is a
+ * file-scope device array of the library, one copy per GPU, held until the process ends.  The
+ * call allocates nothing, frees nothing, never waits for the GPU and records no memset: it only
+ * launches the kernels of pfc_sample on `hip_stream` (a hipStream_t, NULL = the default stream)
+ * of the current device.  Results are those of pfc_sample, bit for bit.
+ *   N                 number of classes, 1 <= N <= 16,777,216 (2^24); more is PFC_EINVAL
+ *   B, r              1 <= B <= 2^20, 0 < r <= 1, and ceil(r*N) >= B so that k = ceil(r*N) is
+ *                     known without reading the labels back (otherwise PFC_EINVAL: that regime
+ *                     needs the synchronising pfc_sample)
+ *   labels, idx_out, labels_local_out (dev), k_out (host), seed, step: as for pfc_sample
+ * A label outside [0, N) is skipped and its labels_local_out entry is -1; there is no context
+ * to report it through.  All calls on one GPU share that GPU's scratch array, which every call
+ * leaves cleared for the next: two calls that overlap in time on one GPU (different streams or
+ * threads) race and give undefined results; calls on one stream, or ordered by events, are fine.
+ */
+int pfc_sample_noalloc(const int64_t* labels, int32_t B, int64_t N, double r,
+                       uint64_t seed, uint64_t step,
+                       int32_t* idx_out, int32_t* labels_local_out, int64_t* k_out,
+                       void* hip_stream);
+
+/*
  * pfc_forward_backward -- loss and gradients of the margin-based softmax over S.
  * Eq. 1 (mean over the batch) with cosine logits, the sum running over j in S only (Eq. 4);
  * the label logit carries the additive angular margin:  z_ij = s*cos_ij for j != y_i,

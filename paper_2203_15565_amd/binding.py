@@ -25,6 +25,7 @@ MARGIN_COSFACE = 1
 
 EXPORTS = [
     "pfc_create", "pfc_destroy", "pfc_num_sampled", "pfc_sample", "pfc_sample_masked",
+    "pfc_sample_noalloc",
     "pfc_forward_backward", "pfc_forward_backward_ex", "pfc_forward_backward_update", "pfc_update", "pfc_check", "pfc_set_timing", "pfc_get_timing",
     "pfc_strerror", "pfc_last_hip_error", "pfc_probe_stream_copy", "pfc_probe_mfma_bf16",
 ]
@@ -65,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.pfc_sample.restype = c.c_int
     lib.pfc_sample_masked.argtypes = [vp, vp, i32, f64, u64, u64, u32, vp, vp, c.POINTER(i64)]
     lib.pfc_sample_masked.restype = c.c_int
+    lib.pfc_sample_noalloc.argtypes = [vp, i32, i64, f64, u64, u64, vp, vp, c.POINTER(i64), vp]
+    lib.pfc_sample_noalloc.restype = c.c_int
     lib.pfc_forward_backward.argtypes = [vp, vp, vp, vp, i64, vp, i32, f32, f32, vp, vp, vp]
     lib.pfc_forward_backward.restype = c.c_int
     lib.pfc_forward_backward_ex.argtypes = [vp, vp, vp, vp, i64, vp, i32, f32, f32, i32, f32, vp, vp,
@@ -99,6 +102,21 @@ def _ptr(t) -> int:
 
 def pfc_num_sampled(N: int, B: int, r: float) -> int:
     return int(load().pfc_num_sampled(N, B, float(r)))
+
+
+def pfc_sample_noalloc(labels, N: int, r: float, seed: int, step: int, idx_out, labels_local_out,
+                       stream: Optional[int] = None) -> int:
+    """pfc_sample without a context and without any allocation (static device scratch); returns k."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    k = ctypes.c_int64(0)
+    rc = load().pfc_sample_noalloc(_ptr(labels), labels.numel(), N, float(r), seed, step,
+                                   _ptr(idx_out), _ptr(labels_local_out), ctypes.byref(k),
+                                   ctypes.c_void_p(stream))
+    if rc != PFC_OK:
+        raise PfcError(rc, "pfc_sample_noalloc")
+    return int(k.value)
 
 
 class Context:

@@ -7,6 +7,9 @@
 // scores are found by a three-pass radix select (8 + 12 + 12 bits), equal scores going to the
 // smaller class id; an index-ordered compaction then writes S in ascending class id.
 #include <math.h>
+#include <string.h>
+
+#include <mutex>
 
 #include "pfc_common.h"
 
@@ -419,3 +422,77 @@ int sample_impl(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t
 }
 
 }  // namespace pfc
+
+// ---------------------------------------------------------------------------------------------
+// pfc_sample_noalloc: pfc_sample for callers that cannot allocate.  The sampler's scratch (the
+// "is in the batch" bitmap, the radix histograms, the select state, the per-block counts and an
+// error word) lives in ONE file-scope device array per GPU instead of a context's hipMalloc'ed
+// buffers; the kernels are those of pfc_sample and take its pieces as pointers.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int64_t kNoallocMaxN = (int64_t)1 << 24;                               // 16,777,216 classes
+constexpr size_t kNaBitmapWords = (size_t)(kNoallocMaxN / 32) + 64;              // as pfc_create sizes it
+constexpr size_t kNaHistWords = 3 * 4096;
+constexpr size_t kNaSelWords = 64;                                               // SelState, 256-byte slot
+constexpr size_t kNaBlkWords = 2 * (size_t)(kNoallocMaxN / pfc::kClassesPerBlock);
+constexpr size_t kNaErrWords = 64;
+constexpr size_t kNaOffHist = kNaBitmapWords;
+constexpr size_t kNaOffSel = kNaOffHist + kNaHistWords;
+constexpr size_t kNaOffBlk = kNaOffSel + kNaSelWords;
+constexpr size_t kNaOffErr = kNaOffBlk + kNaBlkWords;
+constexpr size_t kNaWords = kNaOffErr + kNaErrWords;                             // 2.2 MB
+static_assert(sizeof(pfc::SelState) <= kNaSelWords * 4, "select state slot");
+
+// Zero when the code object is loaded; afterwards every call leaves it zero again (the last
+// reader of each piece clears it, see above), except the error word, which only ever gains bits.
+static __device__ __align__(256) uint32_t scratch[kNaWords];
+
+constexpr int kNaMaxDevices = 64;
+std::mutex g_na_mutex;
+uint32_t* g_na_ptr[kNaMaxDevices];   // device address of `scratch` on each GPU, once looked up
+
+// The array's name is only a host-side handle: its address on the current device comes from the
+// runtime, once per device, and is what the kernels are given.
+int noalloc_scratch(uint32_t** out) {
+  int dev = -1;
+  PFC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kNaMaxDevices) return PFC_EINVAL;
+  std::lock_guard<std::mutex> lock(g_na_mutex);
+  if (!g_na_ptr[dev]) {
+    uint32_t* p = nullptr;
+    PFC_HIP(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    if (!p) return PFC_EHIP;
+    g_na_ptr[dev] = p;
+  }
+  *out = g_na_ptr[dev];
+  return PFC_OK;
+}
+
+}  // namespace
+
+extern "C" int pfc_sample_noalloc(const int64_t* labels, int32_t B, int64_t N, double r,
+                                  uint64_t seed, uint64_t step, int32_t* idx_out,
+                                  int32_t* labels_local_out, int64_t* k_out, void* hip_stream) {
+  if (!labels || !idx_out || !labels_local_out || !k_out) return PFC_EINVAL;
+  if (N < 1 || N > kNoallocMaxN) return PFC_EINVAL;
+  if (B < 1 || B > (1 << 20)) return PFC_EINVAL;
+  if (!(r > 0.0) || !(r <= 1.0)) return PFC_EINVAL;
+  // k must be known without reading anything back: no waiting, no pinned buffer
+  if ((int64_t)ceil(r * (double)N) < (int64_t)B) return PFC_EINVAL;
+  uint32_t* base = nullptr;
+  const int rc = noalloc_scratch(&base);
+  if (rc != PFC_OK) return rc;
+  pfc_ctx c;   // a view of the static scratch on the stack: nothing is allocated, nothing kept
+  memset(&c, 0, sizeof(c));
+  c.N = N;
+  c.stream = (hipStream_t)hip_stream;
+  c.pos_bits = base;
+  c.hist = base + kNaOffHist;
+  c.sel = reinterpret_cast<pfc::SelState*>(base + kNaOffSel);
+  c.blk_cnt = base + kNaOffBlk;
+  c.nblk_cap = (int32_t)(kNoallocMaxN / pfc::kClassesPerBlock);
+  c.err_flag = reinterpret_cast<int32_t*>(base + kNaOffErr);
+  return pfc::sample_impl(&c, labels, B, r, seed, step, 0xFFFFFFFFu, idx_out, labels_local_out,
+                          k_out);
+}
