@@ -66,7 +66,8 @@ int pfc_destroy(pfc_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   void* bufs[] = {c->pos_bits, c->hist, c->sel, c->blk_cnt, c->err_flag, c->Xn,
                   c->Xs, c->rnormX, c->Wn, c->rnormW, c->head, c->E, c->rowpart, c->rowmaxpart, c->rowmax,
-                  c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart, c->dlab, c->dWtmp};
+                  c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart, c->dlab, c->dWtmp,
+                  c->spare};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -144,6 +145,7 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(dXpart, (size_t)kMaxSplits * Bp * Dz * 4);
   ALLOC(dlab, Bp * Dz * 4);
   ALLOC(dWtmp, (size_t)c->k_cap * Dz * 4);
+  ALLOC(spare, 2 * Dz * 4);
 #undef ALLOC
   if (rc == PFC_OK) {
     hipError_t e = hipHostMalloc((void**)&c->host_pin, 64, hipHostMallocDefault);
@@ -157,6 +159,7 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
     hipError_t e = hipMemsetAsync(c->pos_bits, 0, ((size_t)(N + 31) / 32 + 64) * 4, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->hist, 0, 3 * 4096 * 4, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->sel, 0, sizeof(SelState), c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->spare, 0, 2 * Dz * 4, c->stream);
     if (e != hipSuccess) {
       set_hip_error(e, "hipMemsetAsync(sampler scratch)");
       rc = PFC_EHIP;

@@ -94,6 +94,8 @@ struct pfc_ctx {
   float* dXpart;   // [splits x Bp x D]
   float* dlab;     // [Bp x D] label-column part of dWn, one row per first sample of a class (fused step)
   float* dWtmp;    // [k_cap x D] dWn of the fused step whenever its one-kernel form does not apply
+  float* spare;    // [2 x D] a row of zeros (never written) and a row that only takes the stores of
+                   // padding rows (fused step)
 
   // timing
   int32_t num_cu;   // compute units of the device
@@ -161,10 +163,27 @@ int update_impl(pfc_ctx* ctx, float* W, float* v, const int32_t* idx, int64_t k,
 // Device helpers
 // ---------------------------------------------------------------------------------------------
 #if defined(__HIPCC__)
+// Sum over the 64 lanes of a wavefront, the same bits in every lane.  Inside each row of 16
+// lanes the exchange runs through the cross-lane modifiers of the vector ALU (xor 1, xor 2, mirror
+// of 8, mirror of 16: every lane of a row adds the same pairs, and a + b == b + a, so the row's 16
+// lanes end with one value); the four row sums are then read out lane by lane and added in a
+// fixed order.  No LDS round trip (a shuffle-based butterfly costs six of them in a chain).
+template <int CTRL>
+__device__ __forceinline__ float dpp_xadd(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true);
+  return v + __builtin_bit_cast(float, moved);
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v = dpp_xadd<0xB1>(v);    // quad_perm [1,0,3,2]
+  v = dpp_xadd<0x4E>(v);    // quad_perm [2,3,0,1]
+  v = dpp_xadd<0x141>(v);   // row_half_mirror
+  v = dpp_xadd<0x140>(v);   // row_mirror
+  const int b = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+  return (r0 + r1) + (r2 + r3);
 }
 
 template <typename T>

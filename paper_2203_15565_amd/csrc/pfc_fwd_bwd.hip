@@ -24,6 +24,30 @@
 #include "pfc_common.h"
 #include "pfc_gemm.h"
 
+// Phase clocks for tuning, compiled in only with -DPFC_PHASES (never in the shipped library):
+// thread 0 of every workgroup of the selected kernel stores the constant-rate clock at up to 8
+// points.  Kernel tags: 1 logits, 2 dweight, 3 dweight+update.
+#ifdef PFC_PHASES
+__device__ unsigned long long pfc_phase_buf[32768 * 8];
+__device__ int pfc_phase_sel;
+#define PFC_PHASE(tag, slot)                                                               \
+  do {                                                                                     \
+    if (threadIdx.x == 0 && blockIdx.x < 32768 && pfc_phase_sel == (tag))                  \
+      pfc_phase_buf[blockIdx.x * 8 + (slot)] = __builtin_amdgcn_s_memrealtime();               \
+  } while (0)
+extern "C" int pfc_debug_phases(unsigned long long* host_out, int n) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(pfc_phase_buf), (size_t)n * 8);
+}
+extern "C" int pfc_debug_select(int tag) {
+  void* p = nullptr;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(pfc_phase_buf)) != hipSuccess) return -1;
+  if (hipMemset(p, 0, sizeof(unsigned long long) * 32768 * 8) != hipSuccess) return -2;
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(pfc_phase_sel), &tag, sizeof(int));
+}
+#else
+#define PFC_PHASE(tag, slot)
+#endif
+
 namespace pfc {
 
 namespace {
@@ -261,7 +285,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
 
   f32x16 acc[Cfg::TM][Cfg::TN];
   zero_acc<Cfg>(acc);
+  PFC_PHASE(1, 0);
   gemm_tile<Cfg>(Wn + j0 * D, D, Xn + (int64_t)i0 * D, D, D / Cfg::BK, smem, acc);
+  PFC_PHASE(1, 1);
 
   constexpr bool kStage = (sizeof(T) == 2);          // bf16: transpose the tile through LDS
   constexpr int SX = Cfg::BM * 2 + 8;                // staging row (one sample) stride in bytes
@@ -300,6 +326,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
     logits_epilogue_columns<Cfg, false, EXTRAS>(acc, j0, i0, B, klim, kp, ylane, lp, smem, SX, E,
                                                 clabel, colsum, colmax);
 
+  PFC_PHASE(1, 2);
   // cross-wave reduction over the WM wavefronts that share a column (fixed order)
   float* red = reinterpret_cast<float*>(smem + RED_OFF);   // [WM][BN] sums, then [WM][BN] maxima
   if (lane < 32) {
@@ -335,6 +362,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
                                   reinterpret_cast<u32x2*>(E + (int64_t)(i0 + row) * kp + j0 + l * 4));
     }
   }
+  PFC_PHASE(1, 3);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -435,7 +463,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_kernel(
   const int64_t i0 = (int64_t)sp * slabs_per * Cfg::BK;   // first sample of this slice
   f32x16 acc[Cfg::TM][Cfg::TN];
   zero_acc<Cfg>(acc);
+  PFC_PHASE(2, 0);
   gemm_tile<Cfg>(E + i0 * kp + j0, kp, Xs + i0 * D + d0, D, ns, smem, acc);
+  PFC_PHASE(2, 1);
   float* dst = SPLIT ? out + (int64_t)sp * kp * D : out;
 #pragma unroll
   for (int bm = 0; bm < Cfg::TM; ++bm)
@@ -448,6 +478,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_kernel(
           dst[j * D + d0 + acc_col<Cfg>(bn)] = acc[bm][bn][r];
       }
     }
+  PFC_PHASE(2, 2);
 }
 
 // dW[j][d] = sum over slices of part[slice][j][d], in slice order.
@@ -578,8 +609,8 @@ __device__ __forceinline__ void fused_update_tile(
     int64_t j0, char* smem, const typename Cfg::elem* __restrict__ E,
     const typename Cfg::elem* __restrict__ Xs, int64_t k, int64_t kp, int Bp,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ head,
-    const float* __restrict__ lab, float* __restrict__ W, float* __restrict__ V, int64_t N,
-    float lr, float mu, int32_t* __restrict__ err_flag) {
+    const float* __restrict__ lab, float* spare, float* __restrict__ W, float* __restrict__ V,
+    int64_t N, float lr, float mu, int32_t* __restrict__ err_flag) {
   using FL = FusedUpdateLds<Cfg>;
   constexpr int D = Cfg::BN, NC = D / 256, HR = FL::HR, SROW = FL::SROW;
   constexpr int WAVES = Cfg::THREADS / 64, RPW = HR / WAVES;   // rows per wavefront and half
@@ -587,6 +618,14 @@ __device__ __forceinline__ void fused_update_tile(
   constexpr int WIN = 4;                                        // rows of W and v in flight
   static_assert(D % 256 == 0 && HR % WAVES == 0 && ROWS <= 64 && WIN <= ROWS, "fused update geometry");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // Two spare rows of D floats: the first holds zeros (never written) and is what a center that
+  // is nobody's label reads instead of a label part, and what a padding row of the last tile
+  // reads instead of W and v; the second takes the stores of the padding rows and is never read.
+  // Every row thus issues the same loads and stores in the same order with no branch in between,
+  // which is what lets the wait for row n's operands leave the younger requests of rows
+  // n+1 .. n+WIN in flight.
+  const float* zero_row = spare;
+  float* trash_row = spare + D;
 
   // Row n of this wavefront (n = h*RPW + q) is tile row h*HR + q*WAVES + wave: neighbouring
   // wavefronts take neighbouring rows.  Lane n fetches its class id and label head now, so that
@@ -606,24 +645,25 @@ __device__ __forceinline__ void fused_update_tile(
 
   f32x16 acc[Cfg::TM][Cfg::TN];
   zero_acc<Cfg>(acc);
+  PFC_PHASE(3, 0);
   gemm_tile<Cfg>(E + j0, kp, Xs, D, Bp / Cfg::BK, smem, acc);
+  PFC_PHASE(3, 1);
 
-  // A window of WIN rows of W and v is kept in flight: the loads of row n+WIN are issued as soon
-  // as row n has been used, across the two halves.  (Native vector types: arrays of them stay in
-  // registers.)
-  f32x4 w[WIN][NC], v[WIN][NC];
+  // A window of WIN rows of W, v and the label part is kept in flight: the loads of row n+WIN
+  // are issued as soon as row n has been used, across the two halves.  (Native vector types:
+  // arrays of them stay in registers.)
+  f32x4 w[WIN][NC], v[WIN][NC], lb[WIN][NC];
   auto request = [&](int n) {
     const int64_t row = __builtin_amdgcn_readlane(idxv, n);   // wave-uniform
-    const int64_t off = row * D + lane * 4;
+    const int hd = __builtin_amdgcn_readlane(headv, n);
+    const float* wsrc = row >= 0 ? W + row * D : zero_row;    // scalar selects, no branch
+    const float* vsrc = row >= 0 ? V + row * D : zero_row;
+    const float* lsrc = hd != INT_MAX ? lab + (int64_t)hd * D : zero_row;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      if (row >= 0) {   // padding or a bad id: nothing is read (and nothing written below)
-        w[n % WIN][c] = *reinterpret_cast<const f32x4*>(W + off + c * 256);
-        v[n % WIN][c] = *reinterpret_cast<const f32x4*>(V + off + c * 256);
-      } else {
-        w[n % WIN][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-        v[n % WIN][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-      }
+      w[n % WIN][c] = *reinterpret_cast<const f32x4*>(wsrc + c * 256 + lane * 4);
+      v[n % WIN][c] = *reinterpret_cast<const f32x4*>(vsrc + c * 256 + lane * 4);
+      lb[n % WIN][c] = *reinterpret_cast<const f32x4*>(lsrc + c * 256 + lane * 4);
     }
   };
 #pragma unroll
@@ -649,19 +689,16 @@ __device__ __forceinline__ void fused_update_tile(
     for (int q = 0; q < RPW; ++q) {
       const int n = h * RPW + q;
       const int64_t row = __builtin_amdgcn_readlane(idxv, n);
-      const int hd = __builtin_amdgcn_readlane(headv, n);
       const int r = q * WAVES + wave;
+      float* wdst = row >= 0 ? W + row * D : trash_row;
+      float* vdst = row >= 0 ? V + row * D : trash_row;
       f32x4 g[NC];
-#pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        const int d = c * 256 + lane * 4;
-        g[c] = *reinterpret_cast<const f32x4*>(stage + r * SROW + d);
-        if (hd != INT_MAX)   // first sample of a class in the batch: add the label part
-          g[c] += *reinterpret_cast<const f32x4*>(lab + (int64_t)hd * D + d);
-      }
       float ww = 0.f, gw = 0.f;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
+        const int d = c * 256 + lane * 4;
+        // GEMM row + label part (zeros unless this center is the label of a sample)
+        g[c] = *reinterpret_cast<const f32x4*>(stage + r * SROW + d) + lb[n % WIN][c];
         const f32x4 wc = w[n % WIN][c];
         ww += wc[0] * wc[0] + wc[1] * wc[1] + wc[2] * wc[2] + wc[3] * wc[3];
         gw += g[c][0] * wc[0] + g[c][1] * wc[1] + g[c][2] * wc[2] + g[c][3] * wc[3];
@@ -670,26 +707,30 @@ __device__ __forceinline__ void fused_update_tile(
       gw = wave_sum(gw);
       const float rn = 1.f / fmaxf(sqrtf(ww), 1e-12f);
       const float t = gw * rn * rn;
-      if (row >= 0) {
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-          const int d = c * 256 + lane * 4;
-          const f32x4 wc = w[n % WIN][c], vc = v[n % WIN][c];
-          f32x4 vn, wq;
+      for (int c = 0; c < NC; ++c) {
+        const int d = c * 256 + lane * 4;
+        const f32x4 wc = w[n % WIN][c], vc = v[n % WIN][c];
+        f32x4 vn, wq;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            vn[e] = mu * vc[e] + (g[c][e] - t * wc[e]) * rn;
-            wq[e] = wc[e] - lr * vn[e];
-          }
-          // not read again before the next step's gather: nontemporal, so that the rows do not
-          // sit dirty in the L2 while the next kernels run
-          __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(V + row * D + d));
-          __builtin_nontemporal_store(wq, reinterpret_cast<f32x4*>(W + row * D + d));
+        for (int e = 0; e < 4; ++e) {
+          vn[e] = mu * vc[e] + (g[c][e] - t * wc[e]) * rn;
+          wq[e] = wc[e] - lr * vn[e];
         }
+        // not read again before the next step's gather: nontemporal, so that the rows do not
+        // sit dirty in the L2 while the next kernels run
+#ifdef PFC_PLAIN_STORE
+        *reinterpret_cast<f32x4*>(vdst + d) = vn;
+        *reinterpret_cast<f32x4*>(wdst + d) = wq;
+#else
+        __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(vdst + d));
+        __builtin_nontemporal_store(wq, reinterpret_cast<f32x4*>(wdst + d));
+#endif
       }
       if (n + WIN < ROWS) request(n + WIN);
     }
     __syncthreads();   // the next half overwrites the staged rows
+    PFC_PHASE(3, 2 + h);
   }
 }
 
@@ -700,18 +741,27 @@ template <class CfgB, class CfgS>
 __global__ __launch_bounds__(CfgB::THREADS) void gemm_dweight_update_kernel(
     const typename CfgB::elem* __restrict__ E, const typename CfgB::elem* __restrict__ Xs,
     int64_t k, int64_t kp, int Bp, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ head, const float* __restrict__ lab, float* __restrict__ W,
-    float* __restrict__ V, int64_t N, float lr, float mu, int32_t* __restrict__ err_flag,
-    int n_big) {
+    const int32_t* __restrict__ head, const float* __restrict__ lab, float* spare,
+    float* __restrict__ W, float* __restrict__ V, int64_t N, float lr, float mu,
+    int32_t* __restrict__ err_flag, int n_big) {
   static_assert(CfgB::THREADS == CfgS::THREADS && CfgB::BN == CfgS::BN, "one launch shape");
   extern __shared__ __align__(16) char smem[];
   const int b = blockIdx.x;
+#ifdef PFC_STAG_SLEEP   // tuning experiment only: delay half of the first round by half a period
+  if (b < 256 && ((b >> 3) & 1)) {
+    const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+    for (int it = 0; it < 200000; ++it) {
+      if (__builtin_amdgcn_s_memrealtime() - t0 > PFC_STAG_SLEEP) break;
+      __builtin_amdgcn_s_sleep(32);
+    }
+  }
+#endif
   if (b < n_big)
-    fused_update_tile<CfgB>((int64_t)b * CfgB::BM, smem, E, Xs, k, kp, Bp, idx, head, lab, W, V,
-                            N, lr, mu, err_flag);
+    fused_update_tile<CfgB>((int64_t)b * CfgB::BM, smem, E, Xs, k, kp, Bp, idx, head, lab, spare,
+                            W, V, N, lr, mu, err_flag);
   else
     fused_update_tile<CfgS>((int64_t)n_big * CfgB::BM + (int64_t)(b - n_big) * CfgS::BM, smem, E,
-                            Xs, k, kp, Bp, idx, head, lab, W, V, N, lr, mu, err_flag);
+                            Xs, k, kp, Bp, idx, head, lab, spare, W, V, N, lr, mu, err_flag);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -998,7 +1048,8 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     const int n_small = (tiles_big - n_big) * (CfgU::BM / CfgUS::BM);
     PFC_LAUNCH(c, KID_GEMM_DW_UPDATE, (gemm_dweight_update_kernel<CfgU, CfgUS>),
                dim3((unsigned)(n_big + n_small)), dim3(CfgU::THREADS), kFusedLds, E, Xs, k, kp, Bp,
-               idx, c->head, c->dlab, upd->W, upd->v, c->N, upd->lr, upd->mu, c->err_flag, n_big);
+               idx, c->head, c->dlab, c->spare, upd->W, upd->v, c->N, upd->lr, upd->mu, c->err_flag,
+               n_big);
   }
   return PFC_OK;
 }

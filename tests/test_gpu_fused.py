@@ -32,6 +32,7 @@ CASES = [
     (400_000, 300, 512, 0.1, binding.PRECISION_BF16, 400_000),  # one kernel, ragged B, k and tail
     (400_000, 300, 512, 0.1, binding.PRECISION_FP32, 60),       # one kernel, heavy duplicates
     (327_680, 256, 512, 0.1, binding.PRECISION_BF16, 327_680),  # one kernel, k = 32768: no tail
+    (1_000_003, 300, 512, 0.1, binding.PRECISION_BF16, 1_000_003),  # one kernel, three rounds of tiles
     (10_000, 128, 512, 0.1, binding.PRECISION_FP32, 10_000),    # too few tiles
     (93_431, 512, 512, 0.1, binding.PRECISION_BF16, 93_431),
     (3_000, 100, 256, 0.1, binding.PRECISION_FP32, 3_000),      # D != 512
