@@ -117,15 +117,16 @@ int pfc_sample_noalloc(const int64_t* labels, int32_t B, int64_t N, double r,
  *   weight         dev, fp32[N x D], read only
  *   idx            dev, int32[k], ascending class ids (as written by pfc_sample)
  *   labels_local   dev, int32[B], each in [0, k)
- *   s, m           scale (0 < s <= 64) and margin (0 <= m < pi)
+ *   s, m           scale (0 < s <= 65536) and margin (0 <= m < pi)
  *   loss_out       dev, fp32[1]
  *   dfeatures_out  dev, fp32[B x D]: dL/dx_i w.r.t. the RAW feature rows
  *   dweight_out    dev, fp32[k x D]: row j is dL/d wn_j, the gradient w.r.t. the L2-NORMALISED
  *                  center idx[j].  pfc_update turns it into the raw-row gradient
  *                  (g - <g,wn> wn)/|W_j| while it has W_j in registers anyway.
  * An out-of-range idx / labels_local entry is skipped and recorded (pfc_check -> PFC_ELABEL).
- * s is limited to 64 because exp(z) is then representable in fp32/bf16 without a running
- * maximum: z lies in [-s, s] by construction.
+ * Up to s = 64 the softmax needs no running maximum (z lies in [-s, s] by construction, so exp(z)
+ * and its sums are representable in fp32/bf16); above, one more pass of the logit GEMM finds each
+ * sample's largest logit first and the softmax runs relative to it (about a fifth more time).
  */
 int pfc_forward_backward(pfc_ctx* ctx, const float* features, const float* weight,
                          const int32_t* idx, int64_t k, const int32_t* labels_local, int32_t B,

@@ -17,7 +17,8 @@ void set_hip_error(hipError_t e, const char* what) {
 
 static const char* const kKernelNames[KID_COUNT] = {
     "sample_mark",  "sample_hist0", "sample_hist1", "sample_hist2", "sample_count",
-    "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_logits",
+    "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_rowmax",
+    "row_ref", "gemm_logits",
     "row_combine",   "gemm_dweight", "dweight_reduce", "dweight_label",
     "gemm_dfeatures", "dfeatures_final", "update", "gemm_dweight_update"};
 
@@ -66,6 +67,7 @@ int pfc_destroy(pfc_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   void* bufs[] = {c->pos_bits, c->hist, c->sel, c->blk_cnt, c->err_flag, c->Xn,
                   c->Xs, c->rnormX, c->Wn, c->rnormW, c->head, c->E, c->rowpart, c->rowmaxpart, c->rowmax,
+                  c->rowref,
                   c->clabel, c->rowscale, c->dlabel, c->lossrow, c->dXpart, c->dlab, c->dWtmp,
                   c->spare};
   for (void* b : bufs)
@@ -138,6 +140,7 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(rowpart, (kp / kPadK) * 2 * Bp * 4);
   ALLOC(rowmaxpart, (kp / kPadK) * 2 * Bp * 4);
   ALLOC(rowmax, Bp * 4);
+  ALLOC(rowref, Bp * 4);
   ALLOC(clabel, Bp * 4);
   ALLOC(rowscale, Bp * 4);
   ALLOC(dlabel, Bp * 4);
@@ -242,7 +245,7 @@ int pfc_forward_backward_ex(pfc_ctx* c, const float* X, const float* W, const in
   if (!c || !X || !W || !idx || !yl || !loss_out || !dX_out || !dW_out) return PFC_EINVAL;
   if (B < 1 || B > c->B_max) return PFC_EINVAL;
   if (k < 1 || k > c->k_cap || k > c->N) return PFC_EINVAL;
-  if (!(s > 0.f) || !(s <= 64.f)) return PFC_EINVAL;
+  if (!(s > 0.f) || !(s <= 65536.f)) return PFC_EINVAL;
   if (margin_type != PFC_MARGIN_ARCFACE && margin_type != PFC_MARGIN_COSFACE) return PFC_EINVAL;
   if (!(m >= 0.f) || !(m < 3.14159265f)) return PFC_EINVAL;
   if (!(filter_threshold == filter_threshold) || filter_threshold < -1.f) return PFC_EINVAL;
@@ -258,7 +261,7 @@ int pfc_forward_backward_update(pfc_ctx* c, const float* X, float* W, float* v,
   if (!c || !X || !W || !v || !idx || !yl || !loss_out || !dX_out) return PFC_EINVAL;
   if (B < 1 || B > c->B_max) return PFC_EINVAL;
   if (k < 1 || k > c->k_cap || k > c->N) return PFC_EINVAL;
-  if (!(s > 0.f) || !(s <= 64.f)) return PFC_EINVAL;
+  if (!(s > 0.f) || !(s <= 65536.f)) return PFC_EINVAL;
   if (margin_type != PFC_MARGIN_ARCFACE && margin_type != PFC_MARGIN_COSFACE) return PFC_EINVAL;
   if (!(m >= 0.f) || !(m < 3.14159265f)) return PFC_EINVAL;
   if (!(filter_threshold == filter_threshold) || filter_threshold < -1.f) return PFC_EINVAL;

@@ -29,6 +29,8 @@ enum KernelId {
   KID_SAMPLE_REMAP,
   KID_NORM_X,
   KID_GATHER_W,
+  KID_GEMM_ROWMAX,
+  KID_ROW_REF,
   KID_GEMM_LOGITS,
   KID_ROW_COMBINE,
   KID_GEMM_DW,
@@ -87,6 +89,7 @@ struct pfc_ctx {
   float* rowpart;  // [Bp x tiles_j] partial row sums of exp(z)
   float* rowmaxpart;  // [Bp x tiles_j] partial row maxima of the non-label cosines (options)
   float* rowmax;   // [Bp]
+  float* rowref;   // [Bp] largest logit of every sample (scales above 64 only)
   float* clabel;   // [Bp] cosine of the label column
   float* rowscale; // [Bp] s/(B*l_i)
   float* dlabel;   // [Bp] (s/B)(p_iy - 1) rho_i

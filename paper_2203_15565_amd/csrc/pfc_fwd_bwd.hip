@@ -198,7 +198,9 @@ struct LossParams {
   float m, cos_m, sin_m;
   int32_t cosface;   // 0: label logit s*cos(theta+m); 1: s*(cos(theta) - m)
   float tau;         // filter threshold (entries with cosine > tau are dropped); >= 1: off
-  int32_t extras;    // filter and/or column maxima requested
+  int32_t extras;    // filter, column maxima and/or a per-sample reference requested
+  const float* rowref;   // [Bp] largest logit of every sample, or null: exp(z - rowref_i) instead
+                         // of exp(z) (scales above 64, where exp(z) could leave the fp32 range)
 };
 
 __device__ __forceinline__ float label_logit(const LossParams& lp, float c) {
@@ -221,6 +223,9 @@ __device__ __forceinline__ void logits_epilogue_columns(
     const bool vi = i < B;
     const int yloc = ylane[bn];
     float sum = 0.f, clab = 0.f, cmax = -2.f;
+    float ref = 0.f;
+    if constexpr (EXTRAS) ref = lp.rowref ? lp.rowref[i] : 0.f;   // i < Bp: padded entries are 0
+    const float ref2 = ref * 1.44269504088896340736f;
 #pragma unroll
     for (int bm = 0; bm < Cfg::TM; ++bm) {
 #pragma unroll
@@ -230,7 +235,9 @@ __device__ __forceinline__ void logits_epilogue_columns(
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float c = __builtin_amdgcn_fmed3f(acc[bm][bn][g4 * 4 + e], -1.f, 1.f);
-          float ev = __builtin_amdgcn_exp2f(c * lp.s_log2e);   // exp(s*c); |s*c*log2(e)| <= 93
+          // exp(s*c), |s*c*log2(e)| <= 93 without a reference; exp(s*c - ref) <= 1 with one
+          float ev = EXTRAS ? __builtin_amdgcn_exp2f(fmaf(c, lp.s_log2e, -ref2))
+                            : __builtin_amdgcn_exp2f(c * lp.s_log2e);
           if constexpr (GUARDED) {
             const bool lab = (jl + e == yloc);
             const bool neg = vi && jl + e < klim && !lab;      // a real, non-label entry
@@ -261,7 +268,7 @@ __device__ __forceinline__ void logits_epilogue_columns(
     if constexpr (GUARDED) {
       if (yloc >= 0) {   // this lane holds sample i's label entry: it was left out of `sum`
         clabel[i] = clab;
-        sum += __expf(label_logit(lp, clab));
+        sum += __expf(label_logit(lp, clab) - ref);
       }
     }
     sum += __shfl_xor(sum, 32, 64);
@@ -366,6 +373,74 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// gemm_rowmax (scales above 64 only): the logits GEMM once more, in front of gemm_logits, with an
+// epilogue that keeps nothing but the largest logit of every sample in every tile (label entry
+// with its margin); row_ref reduces the tiles.  The softmax then runs relative to that maximum,
+// as an online softmax would, and works for any scale; at s <= 64 a zero reference is exact as
+// well and this pass is skipped.
+// ---------------------------------------------------------------------------------------------
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void gemm_rowmax_kernel(
+    const typename Cfg::elem* __restrict__ Wn, const typename Cfg::elem* __restrict__ Xn, int D,
+    int64_t k, int B, const int32_t* __restrict__ yl, LossParams lp,
+    float* __restrict__ rowmaxpart, int tiles_j, int tiles_i) {
+  extern __shared__ __align__(16) char smem[];
+  int tj, ti;
+  if (!xcd_tile(blockIdx.x, tiles_i, tiles_j, tj, ti)) return;
+  const int64_t j0 = (int64_t)tj * Cfg::BM;
+  const int i0 = ti * Cfg::BN;
+  f32x16 acc[Cfg::TM][Cfg::TN];
+  zero_acc<Cfg>(acc);
+  gemm_tile<Cfg>(Wn + j0 * D, D, Xn + (int64_t)i0 * D, D, D / Cfg::BK, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t krem = k - j0;
+  const int klim = krem < (int64_t)Cfg::BM ? (int)krem : Cfg::BM;
+  float* red = reinterpret_cast<float*>(smem);   // [WM][BN]
+#pragma unroll
+  for (int bn = 0; bn < Cfg::TN; ++bn) {
+    const int i = i0 + acc_col<Cfg>(bn);
+    const int yloc = i < B ? (int)((int64_t)yl[i] - j0) : -1;   // tile row of the label entry
+    float zmax = -3.0e38f;
+#pragma unroll
+    for (int bm = 0; bm < Cfg::TM; ++bm)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int jl = acc_row<Cfg>(bm, r);
+        const float c = __builtin_amdgcn_fmed3f(acc[bm][bn][r], -1.f, 1.f);
+        const bool lab = jl == yloc;
+        const float z = lab ? label_logit(lp, c) : lp.s * c;
+        // entries the filter leaves out of the softmax do not count (the label is never filtered)
+        const bool in = i < B && jl < klim && (lab || !(c > lp.tau));
+        zmax = in ? fmaxf(zmax, z) : zmax;
+      }
+    zmax = fmaxf(zmax, __shfl_xor(zmax, 32, 64));
+    if (lane < 32)
+      red[(wave / Cfg::WN) * Cfg::BN + (wave % Cfg::WN) * Cfg::WTN + bn * 32 + lane] = zmax;
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < Cfg::BN; t += Cfg::THREADS) {
+    float mx = -3.0e38f;
+#pragma unroll
+    for (int w = 0; w < Cfg::WM; ++w) mx = fmaxf(mx, red[w * Cfg::BN + t]);
+    rowmaxpart[(int64_t)(i0 + t) * tiles_j + tj] = mx;
+  }
+}
+
+// rowref[i] = max over the tiles of sample i (0 for padded samples); one wavefront per sample.
+__global__ void row_ref_kernel(const float* __restrict__ rowmaxpart, int tiles_j, int B, int Bp,
+                               float* __restrict__ rowref) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= Bp) return;
+  float mx = -3.0e38f;
+  if (i < B)
+    for (int t = lane; t < tiles_j; t += 64) mx = fmaxf(mx, rowmaxpart[(int64_t)i * tiles_j + t]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  if (lane == 0) rowref[i] = i < B ? mx : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------
 // row_combine: one wavefront per (padded) sample.  l_i = sum of the per-tile partial sums (lane
 // strided, then a fixed shuffle tree: the same order on every run), the per-row scalars, and the
 // row of Xs = (s/(B l_i)) * x_i/|x_i| that feeds the dweight GEMM (zero for padded rows).
@@ -399,10 +474,11 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
       const float c = clabel[i];
       const float sin2 = 1.f - c * c;
       const float zlab = label_logit(lp, c);
-      const float p = __expf(zlab) / l;
+      const float ref = lp.rowref ? lp.rowref[i] : 0.f;   // l is the sum of exp(z - ref)
+      const float p = __expf(zlab - ref) / l;
       // d(label logit)/d cos / s: sin(theta+m)/sin(theta) for the angular margin, 1 for the cosine one
       const float rho = lp.cosface ? 1.f : lp.cos_m + c * lp.sin_m / sqrtf(fmaxf(sin2, kEpsSin2));
-      lossrow[i] = logf(l) - zlab;
+      lossrow[i] = (logf(l) + ref) - zlab;
       rowscale[i] = scale;
       dlabel[i] = (lp.s / (float)B) * (p - 1.f) * rho;
       rowmax[i] = mx;
@@ -615,7 +691,7 @@ __device__ __forceinline__ void fused_update_tile(
   constexpr int D = Cfg::BN, NC = D / 256, HR = FL::HR, SROW = FL::SROW;
   constexpr int WAVES = Cfg::THREADS / 64, RPW = HR / WAVES;   // rows per wavefront and half
   constexpr int ROWS = Cfg::WM * RPW;                           // rows per wavefront and tile
-  constexpr int WIN = 4;                                        // rows of W and v in flight
+  constexpr int WIN = 3;                                        // rows of W, v and label part in flight
   static_assert(D % 256 == 0 && HR % WAVES == 0 && ROWS <= 64 && WIN <= ROWS, "fused update geometry");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // Two spare rows of D floats: the first holds zeros (never written) and is what a center that
@@ -719,13 +795,8 @@ __device__ __forceinline__ void fused_update_tile(
         }
         // not read again before the next step's gather: nontemporal, so that the rows do not
         // sit dirty in the L2 while the next kernels run
-#ifdef PFC_PLAIN_STORE
-        *reinterpret_cast<f32x4*>(vdst + d) = vn;
-        *reinterpret_cast<f32x4*>(wdst + d) = wq;
-#else
         __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(vdst + d));
         __builtin_nontemporal_store(wq, reinterpret_cast<f32x4*>(wdst + d));
-#endif
       }
       if (n + WIN < ROWS) request(n + WIN);
     }
@@ -747,15 +818,6 @@ __global__ __launch_bounds__(CfgB::THREADS) void gemm_dweight_update_kernel(
   static_assert(CfgB::THREADS == CfgS::THREADS && CfgB::BN == CfgS::BN, "one launch shape");
   extern __shared__ __align__(16) char smem[];
   const int b = blockIdx.x;
-#ifdef PFC_STAG_SLEEP   // tuning experiment only: delay half of the first round by half a period
-  if (b < 256 && ((b >> 3) & 1)) {
-    const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
-    for (int it = 0; it < 200000; ++it) {
-      if (__builtin_amdgcn_s_memrealtime() - t0 > PFC_STAG_SLEEP) break;
-      __builtin_amdgcn_s_sleep(32);
-    }
-  }
-#endif
   if (b < n_big)
     fused_update_tile<CfgB>((int64_t)b * CfgB::BM, smem, E, Xs, k, kp, Bp, idx, head, lab, spare,
                             W, V, N, lr, mu, err_flag);
@@ -957,6 +1019,8 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgF, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_rowmax_kernel<CfgF>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgF::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW, true>,
@@ -969,7 +1033,15 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   }
   {
     const int tiles_j = (int)(kp / CfgF::BM), tiles_i = Bp / CfgF::BN;
-    // the options (filter, column maxima) have a kernel of their own: the plain one stays lean
+    if (lp.rowref) {   // scale above 64: the largest logit of every sample first
+      PFC_LAUNCH(c, KID_GEMM_ROWMAX, gemm_rowmax_kernel<CfgF>, dim3(xcd_grid(tiles_i, tiles_j)),
+                 dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, yl, lp, c->rowmaxpart,
+                 tiles_j, tiles_i);
+      PFC_LAUNCH(c, KID_ROW_REF, row_ref_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowmaxpart,
+                 tiles_j, B, Bp, c->rowref);
+    }
+    // the options (filter, column maxima, reference) have a kernel of their own: the plain one
+    // stays lean
     auto logits_kernel = lp.extras ? gemm_logits_kernel<CfgF, true> : gemm_logits_kernel<CfgF, false>;
     PFC_LAUNCH(c, KID_GEMM_LOGITS, logits_kernel, dim3(xcd_grid(tiles_i, tiles_j)),
                dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, Bp, kp, yl, lp, E, c->rowpart,
@@ -1069,7 +1141,10 @@ int forward_backward_impl(pfc_ctx* c, const float* X, const float* W, const int3
   lp.sin_m = sinf(m);
   lp.cosface = margin_type == PFC_MARGIN_COSFACE ? 1 : 0;
   lp.tau = filter_threshold;
-  lp.extras = (filter_threshold < 1.f || stats_out != nullptr) ? 1 : 0;
+  // cosines lie in [-1, 1]: up to s = 64 exp(s*cos) and its row sums stay inside the fp32 (and
+  // bf16) range without a reference; above, the softmax runs relative to each sample's maximum
+  lp.rowref = s > 64.f ? c->rowref : nullptr;
+  lp.extras = (filter_threshold < 1.f || stats_out != nullptr || lp.rowref) ? 1 : 0;
 #define PFC_RUN(T, NC) \
   return run<T, NC>(c, X, W, idx, k, yl, B, lp, loss_out, dX_out, dW_out, stats_out, upd)
   const int nc = c->D / 256;

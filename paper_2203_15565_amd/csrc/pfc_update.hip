@@ -6,54 +6,82 @@
 // 3 row reads (dWn, W, v) and 2 row writes (W, v) of D floats; rows outside idx are never
 // addressed, so they stay bit-identical.
 #include "pfc_common.h"
+#include "pfc_gemm.h"
 
 namespace pfc {
 
 namespace {
 
-template <int NC>
+// RW rows per wavefront, all their loads issued before the first is used.  NT: the gradient is
+// read once and the new rows are not read again before the next step: nontemporal accesses.
+template <int NC, int RW, bool NT>
 __global__ void update_kernel(float* __restrict__ W, float* __restrict__ V, int64_t N,
                               const int32_t* __restrict__ idx, int64_t k,
                               const float* __restrict__ dWn, int D, float lr, float mu,
                               int32_t* __restrict__ err_flag) {
   const int lane = threadIdx.x & 63;
-  const int64_t j = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (j >= k) return;
-  const int64_t row = idx[j];
-  if (row < 0 || row >= N) {
-    if (lane == 0) atomicOr(err_flag, 8);
-    return;
-  }
-  constexpr int nchunk = NC;   // D = 256 * NC
-  float4 w[NC], g[NC], v[NC];
-  float ww = 0.f, gw = 0.f;
+  const int64_t j0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RW;
+  if (j0 >= k) return;
+  f32x4 w[RW][NC], g[RW][NC], v[RW][NC];
+  int64_t rows[RW];
 #pragma unroll
-  for (int c = 0; c < nchunk; ++c) {
-    const int d = c * 256 + lane * 4;
-    w[c] = *reinterpret_cast<const float4*>(W + row * D + d);
-    g[c] = *reinterpret_cast<const float4*>(dWn + j * D + d);
-    v[c] = *reinterpret_cast<const float4*>(V + row * D + d);
-    ww += w[c].x * w[c].x + w[c].y * w[c].y + w[c].z * w[c].z + w[c].w * w[c].w;
-    gw += g[c].x * w[c].x + g[c].y * w[c].y + g[c].z * w[c].z + g[c].w * w[c].w;
+  for (int u = 0; u < RW; ++u) {
+    const int64_t j = j0 + u;
+    rows[u] = -1;
+    if (j < k) {
+      const int64_t row = idx[j];
+      if (row < 0 || row >= N) {
+        if (lane == 0) atomicOr(err_flag, 8);
+      } else {
+        rows[u] = row;
+      }
+    }
   }
-  ww = wave_sum(ww);
-  gw = wave_sum(gw);
-  const float rn = 1.f / fmaxf(sqrtf(ww), 1e-12f);
-  const float t = gw * rn * rn;   // <dWn, wn> / |w|  (multiplies the raw row w)
 #pragma unroll
-  for (int c = 0; c < nchunk; ++c) {
-    const int d = c * 256 + lane * 4;
-    float4 vn, wn;
-    vn.x = mu * v[c].x + (g[c].x - t * w[c].x) * rn;
-    vn.y = mu * v[c].y + (g[c].y - t * w[c].y) * rn;
-    vn.z = mu * v[c].z + (g[c].z - t * w[c].z) * rn;
-    vn.w = mu * v[c].w + (g[c].w - t * w[c].w) * rn;
-    wn.x = w[c].x - lr * vn.x;
-    wn.y = w[c].y - lr * vn.y;
-    wn.z = w[c].z - lr * vn.z;
-    wn.w = w[c].w - lr * vn.w;
-    *reinterpret_cast<float4*>(V + row * D + d) = vn;
-    *reinterpret_cast<float4*>(W + row * D + d) = wn;
+  for (int u = 0; u < RW; ++u) {
+    if (rows[u] < 0) continue;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int d = c * 256 + lane * 4;
+      w[u][c] = *reinterpret_cast<const f32x4*>(W + rows[u] * D + d);
+      if constexpr (NT)
+        g[u][c] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(dWn + (j0 + u) * D + d));
+      else
+        g[u][c] = *reinterpret_cast<const f32x4*>(dWn + (j0 + u) * D + d);
+      v[u][c] = *reinterpret_cast<const f32x4*>(V + rows[u] * D + d);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < RW; ++u) {
+    if (rows[u] < 0) continue;
+    float ww = 0.f, gw = 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const f32x4 wc = w[u][c], gc = g[u][c];
+      ww += wc[0] * wc[0] + wc[1] * wc[1] + wc[2] * wc[2] + wc[3] * wc[3];
+      gw += gc[0] * wc[0] + gc[1] * wc[1] + gc[2] * wc[2] + gc[3] * wc[3];
+    }
+    ww = wave_sum(ww);
+    gw = wave_sum(gw);
+    const float rn = 1.f / fmaxf(sqrtf(ww), 1e-12f);
+    const float t = gw * rn * rn;   // <dWn, wn> / |w|  (multiplies the raw row w)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int d = c * 256 + lane * 4;
+      f32x4 vn, wq;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        vn[e] = mu * v[u][c][e] + (g[u][c][e] - t * w[u][c][e]) * rn;
+        wq[e] = w[u][c][e] - lr * vn[e];
+      }
+      if constexpr (NT) {
+        __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(V + rows[u] * D + d));
+        __builtin_nontemporal_store(wq, reinterpret_cast<f32x4*>(W + rows[u] * D + d));
+      } else {
+        *reinterpret_cast<f32x4*>(V + rows[u] * D + d) = vn;
+        *reinterpret_cast<f32x4*>(W + rows[u] * D + d) = wq;
+      }
+    }
   }
 }
 
@@ -61,13 +89,18 @@ __global__ void update_kernel(float* __restrict__ W, float* __restrict__ V, int6
 
 int update_impl(pfc_ctx* c, float* W, float* v, const int32_t* idx, int64_t k, const float* dW,
                 float lr, float mu) {
-  const int rows_per_block = 4;
+  // measured at the headline workload: nontemporal accesses 0.403 -> 0.384 ms; more rows per
+  // wavefront or other block sizes change nothing
+  constexpr int RW = 1;                          // rows per wavefront
+  constexpr int waves_per_block = 4;
+  const int64_t rows_per_block = (int64_t)RW * waves_per_block;
   const unsigned grid = (unsigned)((k + rows_per_block - 1) / rows_per_block);
   switch (c->D / 256) {
 #define PFC_UPD(NC)                                                                              \
   case NC: {                                                                                     \
-    PFC_LAUNCH(c, KID_UPDATE, update_kernel<NC>, dim3(grid), dim3(rows_per_block * 64), 0, W, v, \
-               c->N, idx, k, dW, c->D, lr, mu, c->err_flag);                                     \
+    PFC_LAUNCH(c, KID_UPDATE, (update_kernel<NC, RW, true>), dim3(grid),                   \
+               dim3(waves_per_block * 64), 0, W, v, c->N, idx, k, dW, c->D, lr, mu,              \
+               c->err_flag);                                                                     \
     return PFC_OK;                                                                               \
   }
     PFC_UPD(1)

@@ -63,11 +63,13 @@ def _fb_parity(precision, N, B, D, r, s, m, seed, wscale=0.01, dup=False):
     rw, nrows = row_rel_max(dWn, o["dWn"])
     _say("   loss", loss, o["loss"], "dX err", ex, "dWn err", ew, "per row: dX", rx, "dWn", rw,
          "rows", nrows, "of", k)
-    assert ex <= GRAD_TOL[precision], ex
-    assert ew <= GRAD_TOL[precision], ew
-    assert rx <= ROW_GRAD_TOL[precision], rx
-    assert rw <= ROW_GRAD_TOL[precision], rw
-    assert nrows >= 0.9 * k
+    amp = max(1.0, s / 64.0)       # the error of a logit is s * (error of the cosine)
+    assert ex <= GRAD_TOL[precision] * amp, ex
+    assert ew <= GRAD_TOL[precision] * amp, ew
+    assert rx <= ROW_GRAD_TOL[precision] * amp, rx
+    assert rw <= ROW_GRAD_TOL[precision] * amp, rw
+    # (at large scales the softmax is so peaked that many rows fall below the floor of the row bar)
+    assert nrows >= (0.9 if s <= 64.0 else 0.5) * k
     # second call on the same context and inputs: bit-identical outputs
     loss2, dX2, dWn2 = gpu_forward_backward(ctx, X, Wd, idx, yl, s, m)
     assert loss2 == loss and dX2.tobytes() == dX.tobytes() and dWn2.tobytes() == dWn.tobytes()
@@ -97,6 +99,16 @@ def test_forward_backward_variants(precision):
     _fb_parity(precision, 4000, 96, 512, 0.1, 64.0, 0.5, seed=13, dup=True)
 
 
+@pytest.mark.parametrize("precision", [binding.PRECISION_FP32, binding.PRECISION_BF16])
+def test_forward_backward_large_scale(precision):
+    """Scales above 64: exp(z) would leave the fp32 range, the softmax runs relative to each
+    sample's largest logit (found by one more pass of the logit GEMM)."""
+    _fb_parity(precision, 10_000, 128, 512, 0.1, 128.0, 0.5, seed=31)
+    _fb_parity(precision, 3000, 100, 256, 0.1, 200.0, 0.3, seed=32)
+    # unit-scale centers close to the features' scale: cosines up to ~0.2, logits spread over 80
+    _fb_parity(precision, 4000, 96, 512, 0.1, 400.0, 0.5, seed=33, dup=True)
+
+
 def test_forward_backward_minimum_k():
     """k = U (no negatives outside the batch), including k far below one tile."""
     _fb_parity(binding.PRECISION_FP32, 100_000, 24, 512, 1e-5, 64.0, 0.5, seed=14)
@@ -113,7 +125,7 @@ def test_forward_backward_einval():
     loss = torch.zeros(1, device="cuda")
     dX = torch.zeros(8, 512, device="cuda")
     dW = torch.zeros(100, 512, device="cuda")
-    for kw in (dict(k=0), dict(k=101), dict(s=65.0), dict(s=0.0), dict(m=-0.1), dict(m=3.2)):
+    for kw in (dict(k=0), dict(k=101), dict(s=1e6), dict(s=0.0), dict(m=-0.1), dict(m=3.2)):
         args = dict(k=100, s=64.0, m=0.5)
         args.update(kw)
         with pytest.raises(binding.PfcError) as e:
