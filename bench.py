@@ -258,8 +258,8 @@ def main() -> int:
     # what this GPU sustains on a plain stream copy (k*D*4 bytes each way) and a bare MFMA loop
     scratch = torch.empty_like(dW)
     measured = {
-        "stream_copy_GBps": round(ctx.pfc_probe_stream_copy(dW, scratch, 10), 1),
-        "mfma_bf16_TFLOPps": round(ctx.pfc_probe_mfma_bf16(5), 1),
+        "stream_copy_GBps": round(binding.pfc_probe_stream_copy(dW, scratch, 10), 1),
+        "mfma_bf16_TFLOPps": round(binding.pfc_probe_mfma_bf16(loss, 5), 1),
     }
     del scratch
     # the vendor GEMM on its best shape (square 8192^3, bf16), as a second yardstick for the MFMA side

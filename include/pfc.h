@@ -201,16 +201,6 @@ int pfc_check(pfc_ctx* ctx);
 int pfc_set_timing(pfc_ctx* ctx, int32_t enabled);
 int pfc_get_timing(pfc_ctx* ctx, const char** names_out, float* ms_out, int32_t cap);
 
-/* Calibration probes for benchmarks (they do not touch any state of the method): what this GPU
- * sustains on a plain float4 stream copy of `bytes` bytes (dev, multiple of 16; the rate counts
- * read + write) and on a bare bf16 MFMA issue loop with non-trivial operand bit patterns.  Both
- * run `reps` times on the context's stream, wait for it, and return the rate through the host
- * pointer.  Reported beside the nominal peaks so that a roofline fraction can be read against
- * both. */
-int pfc_probe_stream_copy(pfc_ctx* ctx, const void* src, void* dst, int64_t bytes, int32_t reps,
-                          double* gbs_out);
-int pfc_probe_mfma_bf16(pfc_ctx* ctx, int32_t reps, double* tflops_out);
-
 const char* pfc_strerror(int code);
 const char* pfc_last_hip_error(void);
 

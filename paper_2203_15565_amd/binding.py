@@ -12,6 +12,7 @@ from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpfc.so")
+PROBE_LIB_PATH = os.path.join(_HERE, "libpfc_probe.so")
 
 PFC_OK = 0
 PFC_EINVAL = -1
@@ -27,8 +28,9 @@ EXPORTS = [
     "pfc_create", "pfc_destroy", "pfc_num_sampled", "pfc_sample", "pfc_sample_masked",
     "pfc_sample_noalloc",
     "pfc_forward_backward", "pfc_forward_backward_ex", "pfc_forward_backward_update", "pfc_update", "pfc_check", "pfc_set_timing", "pfc_get_timing",
-    "pfc_strerror", "pfc_last_hip_error", "pfc_probe_stream_copy", "pfc_probe_mfma_bf16",
+    "pfc_strerror", "pfc_last_hip_error",
 ]
+PROBE_EXPORTS = ["pfc_probe_stream_copy", "pfc_probe_mfma_bf16"]
 
 _lib: Optional[ctypes.CDLL] = None
 
@@ -84,16 +86,60 @@ def load() -> ctypes.CDLL:
     lib.pfc_set_timing.restype = c.c_int
     lib.pfc_get_timing.argtypes = [vp, c.POINTER(c.c_char_p), c.POINTER(f32), i32]
     lib.pfc_get_timing.restype = c.c_int
-    lib.pfc_probe_stream_copy.argtypes = [vp, vp, vp, i64, i32, c.POINTER(f64)]
-    lib.pfc_probe_stream_copy.restype = c.c_int
-    lib.pfc_probe_mfma_bf16.argtypes = [vp, i32, c.POINTER(f64)]
-    lib.pfc_probe_mfma_bf16.restype = c.c_int
     lib.pfc_strerror.argtypes = [c.c_int]
     lib.pfc_strerror.restype = c.c_char_p
     lib.pfc_last_hip_error.argtypes = []
     lib.pfc_last_hip_error.restype = c.c_char_p
     _lib = lib
     return lib
+
+
+_probe_lib: Optional[ctypes.CDLL] = None
+
+
+def load_probe() -> ctypes.CDLL:
+    """Load libpfc_probe.so (the benchmark's calibration probes); raise if it is missing."""
+    global _probe_lib
+    if _probe_lib is None:
+        if not os.path.exists(PROBE_LIB_PATH):
+            raise FileNotFoundError(PROBE_LIB_PATH + " is missing: run "
+                                    "`python -m paper_2203_15565_amd.build` first")
+        lib = ctypes.CDLL(PROBE_LIB_PATH)
+        c = ctypes
+        lib.pfc_probe_stream_copy.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64,
+                                              c.c_int32, c.POINTER(c.c_double)]
+        lib.pfc_probe_stream_copy.restype = c.c_int
+        lib.pfc_probe_mfma_bf16.argtypes = [c.c_void_p, c.c_void_p, c.c_int32,
+                                            c.POINTER(c.c_double)]
+        lib.pfc_probe_mfma_bf16.restype = c.c_int
+        _probe_lib = lib
+    return _probe_lib
+
+
+def _current_stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def pfc_probe_stream_copy(src, dst, reps: int = 10) -> float:
+    """GB/s (read + write) of a plain copy of src into dst (same-size device tensors)."""
+    out = ctypes.c_double(0.0)
+    nbytes = src.numel() * src.element_size()
+    rc = load_probe().pfc_probe_stream_copy(ctypes.c_void_p(_current_stream()), _ptr(src),
+                                            _ptr(dst), nbytes, reps, ctypes.byref(out))
+    if rc != PFC_OK:
+        raise RuntimeError("pfc_probe_stream_copy failed [%d]" % rc)
+    return float(out.value)
+
+
+def pfc_probe_mfma_bf16(sink, reps: int = 5) -> float:
+    """TFLOP/s of a bare bf16 MFMA issue loop (sink: any device float tensor)."""
+    out = ctypes.c_double(0.0)
+    rc = load_probe().pfc_probe_mfma_bf16(ctypes.c_void_p(_current_stream()), _ptr(sink), reps,
+                                          ctypes.byref(out))
+    if rc != PFC_OK:
+        raise RuntimeError("pfc_probe_mfma_bf16 failed [%d]" % rc)
+    return float(out.value)
 
 
 def _ptr(t) -> int:
@@ -213,24 +259,6 @@ class Context:
         rc = load().pfc_set_timing(self._h, 1 if enabled else 0)
         if rc != PFC_OK:
             raise PfcError(rc, "pfc_set_timing")
-
-    def pfc_probe_stream_copy(self, src, dst, reps: int = 10) -> float:
-        """GB/s (read + write) of a plain copy of src into dst (same-size device tensors)."""
-        out = ctypes.c_double(0.0)
-        nbytes = src.numel() * src.element_size()
-        rc = load().pfc_probe_stream_copy(self._h, _ptr(src), _ptr(dst), nbytes, reps,
-                                          ctypes.byref(out))
-        if rc != PFC_OK:
-            raise PfcError(rc, "pfc_probe_stream_copy")
-        return float(out.value)
-
-    def pfc_probe_mfma_bf16(self, reps: int = 5) -> float:
-        """TFLOP/s of a bare bf16 MFMA issue loop."""
-        out = ctypes.c_double(0.0)
-        rc = load().pfc_probe_mfma_bf16(self._h, reps, ctypes.byref(out))
-        if rc != PFC_OK:
-            raise PfcError(rc, "pfc_probe_mfma_bf16")
-        return float(out.value)
 
     def pfc_get_timing(self) -> dict:
         cap = 64

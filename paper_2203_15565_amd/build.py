@@ -1,4 +1,4 @@
-"""Build libpfc.so (hand-written HIP, gfx950 only) in-tree with hipcc.
+"""Build libpfc.so and libpfc_probe.so (hand-written HIP, gfx950 only) in-tree with hipcc.
 
     python -m paper_2203_15565_amd.build        # compiles every source, links the library
 """
@@ -13,7 +13,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpfc.so")
-SOURCES = ["pfc_api.hip", "pfc_sample.hip", "pfc_fwd_bwd.hip", "pfc_update.hip", "pfc_probe.hip"]
+SOURCES = ["pfc_api.hip", "pfc_sample.hip", "pfc_fwd_bwd.hip", "pfc_update.hip"]
+# calibration probes of the benchmark: a library of their own, not part of the product ABI
+PROBE_LIB = os.path.join(HERE, "libpfc_probe.so")
+PROBE_SOURCES = ["pfc_probe.hip"]
 
 # -packed-fp32-ops off: the compiler must not form v_pk_*_f32 from ordinary float code.
 HIPCC_FLAGS = [
@@ -46,6 +49,7 @@ def build(verbose: bool = False) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    probe_objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in PROBE_SOURCES]
 
     def compile_one(pair):
         src, obj = pair
@@ -54,10 +58,11 @@ def build(verbose: bool = False) -> str:
             print(out)
 
     with ThreadPoolExecutor(max_workers=4) as ex:
-        list(ex.map(compile_one, zip(SOURCES, objs)))
-    out = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
-    if verbose and out.strip():
-        print(out)
+        list(ex.map(compile_one, zip(SOURCES + PROBE_SOURCES, objs + probe_objs)))
+    for lib, lobjs in ((LIB, objs), (PROBE_LIB, probe_objs)):
+        out = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *lobjs])
+        if verbose and out.strip():
+            print(out)
     return LIB
 
 

@@ -1,9 +1,15 @@
-// Calibration probes for benchmarks: what this GPU sustains on a plain stream copy and on a bare
-// MFMA issue loop, measured with HIP events on the context's stream.  They are reported next to
-// the nominal peaks (8 TB/s HBM3E, 2.5 PFLOP/s dense bf16) so that a roofline fraction can be
-// read against both.
+// Calibration probes for benchmarks (libpfc_probe.so, not part of libpfc.so): what this GPU
+// sustains on a plain stream copy and on a bare MFMA issue loop, measured with HIP events on the
+// given stream.  They are reported next to the nominal peaks (8 TB/s HBM3E, 2.5 PFLOP/s dense
+// bf16) so that a roofline fraction can be read against both.
 #include "pfc_common.h"
 #include "pfc_gemm.h"
+#include "pfc_probe.h"
+
+namespace pfc {
+// this library has no context: errors are only reported through the return code
+void set_hip_error(hipError_t, const char*) {}
+}  // namespace pfc
 
 namespace pfc {
 namespace {
@@ -60,20 +66,21 @@ using namespace pfc;
 
 extern "C" {
 
-int pfc_probe_stream_copy(pfc_ctx* c, const void* src, void* dst, int64_t bytes, int32_t reps,
-                          double* gbs_out) {
-  if (!c || !src || !dst || !gbs_out || bytes < 16 || bytes % 16 != 0 || reps < 1) return PFC_EINVAL;
+int pfc_probe_stream_copy(void* hip_stream, const void* src, void* dst, int64_t bytes,
+                          int32_t reps, double* gbs_out) {
+  if (!src || !dst || !gbs_out || bytes < 16 || bytes % 16 != 0 || reps < 1) return PFC_EINVAL;
+  hipStream_t stream = (hipStream_t)hip_stream;
   hipEvent_t e0, e1;
   PFC_HIP(hipEventCreate(&e0));
   PFC_HIP(hipEventCreate(&e1));
   const size_t n = (size_t)bytes / 16;
-  hipLaunchKernelGGL(probe_copy_kernel, dim3(65536), dim3(256), 0, c->stream, (const float4*)src,
+  hipLaunchKernelGGL(probe_copy_kernel, dim3(65536), dim3(256), 0, stream, (const float4*)src,
                      (float4*)dst, n);
-  PFC_HIP(hipEventRecord(e0, c->stream));
+  PFC_HIP(hipEventRecord(e0, stream));
   for (int i = 0; i < reps; ++i)
-    hipLaunchKernelGGL(probe_copy_kernel, dim3(65536), dim3(256), 0, c->stream, (const float4*)src,
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(65536), dim3(256), 0, stream, (const float4*)src,
                        (float4*)dst, n);
-  PFC_HIP(hipEventRecord(e1, c->stream));
+  PFC_HIP(hipEventRecord(e1, stream));
   PFC_HIP(hipEventSynchronize(e1));
   float ms = 0.f;
   PFC_HIP(hipEventElapsedTime(&ms, e0, e1));
@@ -83,18 +90,18 @@ int pfc_probe_stream_copy(pfc_ctx* c, const void* src, void* dst, int64_t bytes,
   return PFC_OK;
 }
 
-int pfc_probe_mfma_bf16(pfc_ctx* c, int32_t reps, double* tflops_out) {
-  if (!c || !tflops_out || reps < 1) return PFC_EINVAL;
+int pfc_probe_mfma_bf16(void* hip_stream, float* sink, int32_t reps, double* tflops_out) {
+  if (!sink || !tflops_out || reps < 1) return PFC_EINVAL;
+  hipStream_t stream = (hipStream_t)hip_stream;
   hipEvent_t e0, e1;
   PFC_HIP(hipEventCreate(&e0));
   PFC_HIP(hipEventCreate(&e1));
   const int iters = 2048, blocks = 2048;   // 8 wavefronts per CU at a time, 8192 in total
-  float* sink = c->lossrow;
-  hipLaunchKernelGGL(probe_mfma_kernel, dim3(blocks), dim3(256), 0, c->stream, iters, sink);
-  PFC_HIP(hipEventRecord(e0, c->stream));
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3(blocks), dim3(256), 0, stream, iters, sink);
+  PFC_HIP(hipEventRecord(e0, stream));
   for (int i = 0; i < reps; ++i)
-    hipLaunchKernelGGL(probe_mfma_kernel, dim3(blocks), dim3(256), 0, c->stream, iters, sink);
-  PFC_HIP(hipEventRecord(e1, c->stream));
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(blocks), dim3(256), 0, stream, iters, sink);
+  PFC_HIP(hipEventRecord(e1, stream));
   PFC_HIP(hipEventSynchronize(e1));
   float ms = 0.f;
   PFC_HIP(hipEventElapsedTime(&ms, e0, e1));

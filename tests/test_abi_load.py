@@ -12,8 +12,8 @@ from paper_2203_15565_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "pfc.h")).read()
+def _declared_symbols(header="pfc.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(pfc_[a-z0-9_]+)\s*\(", text)))
 
@@ -27,6 +27,20 @@ def test_header_symbols_are_exported():
     for name in declared:
         assert hasattr(lib, name), name
     assert sorted(binding.EXPORTS) == declared
+
+
+def test_probe_header_symbols_are_exported():
+    if not os.path.exists(binding.PROBE_LIB_PATH):
+        pytest.skip("libpfc_probe.so not built (run python -m paper_2203_15565_amd.build)")
+    lib = ctypes.CDLL(binding.PROBE_LIB_PATH)
+    declared = _declared_symbols("pfc_probe.h")
+    assert declared == sorted(binding.PROBE_EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    # and the product library no longer carries them
+    if os.path.exists(binding.LIB_PATH):
+        prod = ctypes.CDLL(binding.LIB_PATH)
+        assert not any(hasattr(prod, name) for name in declared)
 
 
 def test_num_sampled_host_function():
