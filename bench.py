@@ -30,12 +30,22 @@ PEAK_FP32_MFMA_TFLOPS = 157.3  # fp32 MFMA
 # summarised in profiles/headline_step_hbm_traffic.md, keyed by (workload, r, kernel).  None where
 # no counter run has been recorded.
 MEASURED_TRAFFIC_BYTES: dict = {
-    ("headline", 0.1, "gemm_dweight_update"): 2171192260,
-    ("headline", 0.1, "update"): 2115921901,
-    ("headline", 0.1, "gather_normalize_w"): 636325933,
-    ("headline", 0.1, "gemm_logits"): 679896561,
-    ("headline", 0.1, "gemm_dweight"): 902788764,
-    ("headline", 0.1, "gemm_dfeatures"): 700277303,
+    ("headline", 0.1, "gemm_dweight_update"): 2171336372,
+    ("headline", 0.1, "update"): 2115905488,
+    ("headline", 0.1, "gather_normalize_w"): 636323100,
+    ("headline", 0.1, "gemm_logits"): 682117883,
+    ("headline", 0.1, "gemm_dweight"): 902784708,
+    ("headline", 0.1, "gemm_dfeatures"): 700301524,
+}
+
+# Fraction of a GEMM kernel's own cycles in which an MFMA pipe was busy, from the rocprofv3 --pmc
+# run summarised in profiles/headline_step_mfma_lds_counters.md (SQ_VALU_MFMA_BUSY_CYCLES over
+# the kernel's SQ_BUSY_CYCLES: independent of the clock the kernel ran at).
+MEASURED_MFMA_BUSY: dict = {
+    ("headline", 0.1, "gemm_logits"): 0.331,
+    ("headline", 0.1, "gemm_dweight"): 0.376,
+    ("headline", 0.1, "gemm_dfeatures"): 0.589,
+    ("headline", 0.1, "gemm_dweight_update"): 0.191,
 }
 
 
@@ -235,11 +245,15 @@ def main() -> int:
             if bound == "mfma":
                 ach = amount / (ms * 1e-3) / 1e12
                 ent.update(bound="mfma", achieved=round(ach, 2), peak=peak_mfma, unit="TFLOP/s",
-                           frac=round(ach / peak_mfma, 4))
+                           frac=round(ach / peak_mfma, 4),
+                           mfma_busy_frac=MEASURED_MFMA_BUSY.get((wl.name, wl.r, name)))
             else:
                 ach = amount / (ms * 1e-3) / 1e9
                 ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                           frac=round(ach / PEAK_HBM_GBS, 4))
+                           frac=round(ach / PEAK_HBM_GBS, 4),
+                           traffic=MEASURED_TRAFFIC_BYTES.get((wl.name, wl.r, name)))
+                if name == "gemm_dweight_update":
+                    ent["mfma_busy_frac"] = MEASURED_MFMA_BUSY.get((wl.name, wl.r, name))
         kernels[name] = ent
     # the sampler: integer work only (five sweeps of one Philox4x32-10 block per four classes, about
     # 70 integer operations each), so its yardstick is the integer ALU rate, 256 CUs x 64 lanes x

@@ -12,76 +12,48 @@ namespace pfc {
 
 namespace {
 
-// RW rows per wavefront, all their loads issued before the first is used.  NT: the gradient is
-// read once and the new rows are not read again before the next step: nontemporal accesses.
-template <int NC, int RW, bool NT>
+// The gradient is read once and the new rows are not read again before the next step, so both go
+// through nontemporal accesses (measured at the headline workload: 0.403 -> 0.384 ms; more rows
+// per wavefront or other block sizes change nothing).
+template <int NC>
 __global__ void update_kernel(float* __restrict__ W, float* __restrict__ V, int64_t N,
                               const int32_t* __restrict__ idx, int64_t k,
                               const float* __restrict__ dWn, int D, float lr, float mu,
                               int32_t* __restrict__ err_flag) {
   const int lane = threadIdx.x & 63;
-  const int64_t j0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RW;
-  if (j0 >= k) return;
-  f32x4 w[RW][NC], g[RW][NC], v[RW][NC];
-  int64_t rows[RW];
-#pragma unroll
-  for (int u = 0; u < RW; ++u) {
-    const int64_t j = j0 + u;
-    rows[u] = -1;
-    if (j < k) {
-      const int64_t row = idx[j];
-      if (row < 0 || row >= N) {
-        if (lane == 0) atomicOr(err_flag, 8);
-      } else {
-        rows[u] = row;
-      }
-    }
+  const int64_t j = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (j >= k) return;
+  const int64_t row = idx[j];
+  if (row < 0 || row >= N) {
+    if (lane == 0) atomicOr(err_flag, 8);
+    return;
   }
+  f32x4 w[NC], g[NC], v[NC];
+  float ww = 0.f, gw = 0.f;
 #pragma unroll
-  for (int u = 0; u < RW; ++u) {
-    if (rows[u] < 0) continue;
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int d = c * 256 + lane * 4;
-      w[u][c] = *reinterpret_cast<const f32x4*>(W + rows[u] * D + d);
-      if constexpr (NT)
-        g[u][c] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(dWn + (j0 + u) * D + d));
-      else
-        g[u][c] = *reinterpret_cast<const f32x4*>(dWn + (j0 + u) * D + d);
-      v[u][c] = *reinterpret_cast<const f32x4*>(V + rows[u] * D + d);
-    }
+  for (int c = 0; c < NC; ++c) {   // D = 256 * NC
+    const int d = c * 256 + lane * 4;
+    w[c] = *reinterpret_cast<const f32x4*>(W + row * D + d);
+    g[c] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(dWn + j * D + d));
+    v[c] = *reinterpret_cast<const f32x4*>(V + row * D + d);
+    ww += w[c][0] * w[c][0] + w[c][1] * w[c][1] + w[c][2] * w[c][2] + w[c][3] * w[c][3];
+    gw += g[c][0] * w[c][0] + g[c][1] * w[c][1] + g[c][2] * w[c][2] + g[c][3] * w[c][3];
   }
+  ww = wave_sum(ww);
+  gw = wave_sum(gw);
+  const float rn = 1.f / fmaxf(sqrtf(ww), 1e-12f);
+  const float t = gw * rn * rn;   // <dWn, wn> / |w|  (multiplies the raw row w)
 #pragma unroll
-  for (int u = 0; u < RW; ++u) {
-    if (rows[u] < 0) continue;
-    float ww = 0.f, gw = 0.f;
+  for (int c = 0; c < NC; ++c) {
+    const int d = c * 256 + lane * 4;
+    f32x4 vn, wq;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const f32x4 wc = w[u][c], gc = g[u][c];
-      ww += wc[0] * wc[0] + wc[1] * wc[1] + wc[2] * wc[2] + wc[3] * wc[3];
-      gw += gc[0] * wc[0] + gc[1] * wc[1] + gc[2] * wc[2] + gc[3] * wc[3];
+    for (int e = 0; e < 4; ++e) {
+      vn[e] = mu * v[c][e] + (g[c][e] - t * w[c][e]) * rn;
+      wq[e] = w[c][e] - lr * vn[e];
     }
-    ww = wave_sum(ww);
-    gw = wave_sum(gw);
-    const float rn = 1.f / fmaxf(sqrtf(ww), 1e-12f);
-    const float t = gw * rn * rn;   // <dWn, wn> / |w|  (multiplies the raw row w)
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int d = c * 256 + lane * 4;
-      f32x4 vn, wq;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        vn[e] = mu * v[u][c][e] + (g[u][c][e] - t * w[u][c][e]) * rn;
-        wq[e] = w[u][c][e] - lr * vn[e];
-      }
-      if constexpr (NT) {
-        __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(V + rows[u] * D + d));
-        __builtin_nontemporal_store(wq, reinterpret_cast<f32x4*>(W + rows[u] * D + d));
-      } else {
-        *reinterpret_cast<f32x4*>(V + rows[u] * D + d) = vn;
-        *reinterpret_cast<f32x4*>(W + rows[u] * D + d) = wq;
-      }
-    }
+    __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(V + row * D + d));
+    __builtin_nontemporal_store(wq, reinterpret_cast<f32x4*>(W + row * D + d));
   }
 }
 
@@ -89,18 +61,13 @@ __global__ void update_kernel(float* __restrict__ W, float* __restrict__ V, int6
 
 int update_impl(pfc_ctx* c, float* W, float* v, const int32_t* idx, int64_t k, const float* dW,
                 float lr, float mu) {
-  // measured at the headline workload: nontemporal accesses 0.403 -> 0.384 ms; more rows per
-  // wavefront or other block sizes change nothing
-  constexpr int RW = 1;                          // rows per wavefront
-  constexpr int waves_per_block = 4;
-  const int64_t rows_per_block = (int64_t)RW * waves_per_block;
+  const int rows_per_block = 4;   // one wavefront per row
   const unsigned grid = (unsigned)((k + rows_per_block - 1) / rows_per_block);
   switch (c->D / 256) {
 #define PFC_UPD(NC)                                                                              \
   case NC: {                                                                                     \
-    PFC_LAUNCH(c, KID_UPDATE, (update_kernel<NC, RW, true>), dim3(grid),                   \
-               dim3(waves_per_block * 64), 0, W, v, c->N, idx, k, dW, c->D, lr, mu,              \
-               c->err_flag);                                                                     \
+    PFC_LAUNCH(c, KID_UPDATE, update_kernel<NC>, dim3(grid), dim3(rows_per_block * 64), 0, W, v, \
+               c->N, idx, k, dW, c->D, lr, mu, c->err_flag);                                     \
     return PFC_OK;                                                                               \
   }
     PFC_UPD(1)
