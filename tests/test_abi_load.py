@@ -83,6 +83,27 @@ def test_null_context_is_einval():
     assert lib.pfc_destroy(None) == binding.PFC_EINVAL
 
 
+def test_create_rejects_what_the_header_rules_out():
+    """Argument checks of pfc_create that return before any device call."""
+    if not os.path.exists(binding.LIB_PATH):
+        pytest.skip("libpfc.so not built")
+    lib = binding.load()
+    h = ctypes.c_void_p()
+    bad = [
+        (1000, 300, 64, 0.1, 1),              # D not a multiple of 256
+        (1000, 1280, 64, 0.1, 1),             # D above 1024
+        (0, 512, 64, 0.1, 1), (1 << 31, 512, 64, 0.1, 1),
+        (1000, 512, 0, 0.1, 1), (1000, 512, 64, 0.0, 1), (1000, 512, 64, 1.5, 1),
+        (1000, 512, 64, 0.1, 2),              # unknown precision
+        ((1 << 31) - 1, 512, 1024, 1.0, 1),   # 2^31 sampled classes: beyond the 32-bit staging offsets
+        (1 << 25, 512, 1024, 1.0, 0),         # 2^25 sampled classes with fp32 operands: likewise
+    ]
+    for N, D, B, r, prec in bad:
+        rc = lib.pfc_create(ctypes.byref(h), N, D, B, r, prec, None)
+        assert rc == binding.PFC_EINVAL and not h.value, (N, D, B, r, prec, rc)
+    assert lib.pfc_create(None, 1000, 512, 64, 0.1, 1, None) == binding.PFC_EINVAL
+
+
 def test_library_is_not_older_than_its_sources():
     """Guards against running GPU tests on a stale build: rebuild after touching csrc/."""
     if not os.path.exists(binding.LIB_PATH):

@@ -393,3 +393,115 @@ def test_replay_from_saved_state_is_bit_identical(fused):
     assert not torch.equal(W2, W_saved)
     a.close()
     b.close()
+
+
+@pytest.mark.parametrize("precision", [binding.PRECISION_FP32, binding.PRECISION_BF16])
+def test_features_parallel_to_centers(precision):
+    """Degenerate cosines: some features are exact multiples of a sampled center (cosine +1 with
+    it) or of a negated center (cosine -1), for label and non-label centers alike: the clamp, and
+    the margin derivative sin(theta + m)/sin(theta) at sin(theta) = 0, where the reading with the
+    floor of 1e-12 under the root makes it 4.8e5.  Loss, every output finite, and all gradients and
+    updated centers that do not involve a sample parallel to its OWN label center stay inside the
+    bars; for those samples (and their label centers) the gradient along the common direction is
+    5e5 times the usual size and its projection is the rounding residue of whatever precision
+    computed it, so nothing but finiteness is asserted about them."""
+    torch = _torch()
+    N, B, D, r, s, m = 6000, 96, 512, 0.1, 64.0, 0.5
+    rng = np.random.default_rng(55)
+    X = rng.standard_normal((B, D)).astype(np.float32)
+    W = (rng.standard_normal((N, D)) * 0.01).astype(np.float32)
+    labels = rng.permutation(N)[:B]       # distinct labels: one sample per label center
+    X[0] = 37.0 * W[labels[0]]            # cosine +1 with its own label center
+    X[1] = -5.0 * W[labels[1]]            # cosine -1 with its own label center
+    X[2] = 11.0 * W[labels[3]]            # cosine +1 with another sample's label center
+    X[4] = -2.0 * W[labels[5]]            # cosine -1 with another sample's label center
+    own = np.array([0, 1])                # samples parallel to their own label center
+    ctx = binding.Context(N, D, B, r, precision)
+    idx, yl, k = gpu_sample(ctx, labels, r, 0, 0)
+    idx = idx[:k]
+    Wd = torch.from_numpy(W).cuda()
+    vd = torch.zeros_like(Wd)
+    _say("degenerate cosines", precision)
+    loss, dX, dWn = gpu_forward_backward(ctx, X, Wd, idx, yl, s, m)
+    idx_d = torch.from_numpy(idx).cuda()
+    ctx.pfc_update(Wd, vd, idx_d, k, torch.from_numpy(dWn).cuda(), 0.1, 0.9)
+    torch.cuda.synchronize()
+    assert ctx.pfc_check() == binding.PFC_OK
+    sel = idx.astype(np.int64)
+    o = O.forward_backward(X, W[sel], yl, s, m)
+    assert abs(o["cos"]).max() == 1.0                       # the case is what it claims to be
+    Wg, vg = Wd.cpu().numpy(), vd.cpu().numpy()
+    assert np.isfinite(dX).all() and np.isfinite(dWn).all() and np.isfinite(loss)
+    assert np.isfinite(Wg).all() and np.isfinite(vg).all()
+    assert abs(loss - o["loss"]) <= LOSS_TOL[precision] * abs(o["loss"]), (loss, o["loss"])
+    ok_s = np.setdiff1d(np.arange(B), own)                  # samples
+    ok_c = np.setdiff1d(np.arange(k), yl[own])              # positions in the sampled set
+    assert rel_max(dX[ok_s], o["dX"][ok_s]) <= GRAD_TOL[precision]
+    assert rel_max(dWn[ok_c], o["dWn"][ok_c]) <= GRAD_TOL[precision]
+    W64, v64 = W.astype(np.float64), np.zeros((N, D))
+    O.update(W64, v64, sel, o["dW"], 0.1, 0.9)
+    rows = sel[ok_c]
+    err = row_rel_err(Wg[rows], W64[rows], np.linalg.norm(W64[rows], axis=1))
+    _say("   loss", loss, o["loss"], "W row err", err)
+    assert err <= W_TOL
+    assert rel_max(vg[rows], v64[rows]) <= GRAD_TOL[precision]
+    rest = np.setdiff1d(np.arange(N), sel)
+    assert Wg[rest].tobytes() == W[rest].tobytes() and not vg[rest].any()
+    ctx.close()
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_step_under_graph_capture(fused):
+    """A whole step recorded into a HIP graph (the library allocates nothing, records no memset and
+    never waits for the GPU when ceil(r N) >= B) and replayed several times, with eager work and
+    synchronisations in between: every replay from a given (W, v) gives the bits of the eager step."""
+    torch = _torch()
+    wl = workloads.CONFIGS["medium"].with_(N=340_000 if fused else 93_431)
+    rng = np.random.default_rng(7)
+    W0 = torch.from_numpy((rng.standard_normal((wl.N, wl.D)) * 0.01).astype(np.float32)).cuda()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ctx = binding.Context(wl.N, wl.D, wl.B, wl.r, wl.precision)
+        cap = binding.pfc_num_sampled(wl.N, wl.B, wl.r)
+        idx = torch.zeros(cap, dtype=torch.int32, device="cuda")
+        yl = torch.zeros(wl.B, dtype=torch.int32, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        dX = torch.zeros(wl.B, wl.D, device="cuda")
+        dW = torch.zeros(cap, wl.D, device="cuda")
+        X = torch.from_numpy(workloads.make_features(wl, 0)).cuda()
+        lab = torch.from_numpy(workloads.make_labels(wl, 0)).cuda()
+        Wd, vd = W0.clone(), torch.zeros_like(W0)
+
+        def step():
+            k = ctx.pfc_sample(lab, wl.r, wl.seed, 0, idx, yl)
+            if fused:
+                ctx.pfc_forward_backward_update(X, Wd, vd, idx, k, yl, wl.s, wl.m, wl.lr, wl.mu,
+                                                loss, dX)
+            else:
+                ctx.pfc_forward_backward(X, Wd, idx, k, yl, wl.s, wl.m, loss, dX, dW)
+                ctx.pfc_update(Wd, vd, idx, k, dW, wl.lr, wl.mu)
+
+        _say("graph capture", "fused" if fused else "three calls")
+        step()                                   # eager: also raises the kernels' LDS limits
+        stream.synchronize()
+        Wd.copy_(W0)
+        vd.zero_()
+        step()
+        stream.synchronize()
+        ref = (Wd.clone(), vd.clone(), loss.clone(), dX.clone())
+        graph = torch.cuda.CUDAGraph()
+        Wd.copy_(W0)
+        vd.zero_()
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+        for rep in range(3):
+            Wd.copy_(W0)                         # eager work between the replays
+            vd.zero_()
+            loss.fill_(-1.0)
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            for got, want in zip((Wd, vd, loss, dX), ref):
+                assert torch.equal(got.view(torch.int32), want.view(torch.int32)), rep
+        assert ctx.pfc_check() == binding.PFC_OK
+        ctx.close()
