@@ -257,7 +257,7 @@ def main() -> int:
         kernels[name] = ent
     # the sampler: integer work only (five sweeps of one Philox4x32-10 block per four classes, about
     # 70 integer operations each), so its yardstick is the integer ALU rate, 256 CUs x 64 lanes x
-    # 2.4 GHz = 39.3 Tops/s; in practice it is bound by its seven dependent launches
+    # 2.4 GHz = 39.3 Tops/s; in practice it is bound by its six dependent launches
     samp_ms = sum(ms for n, ms in kern_ms.items() if n.startswith("sample_"))
     samp_ops = 5.0 * (wl.N / 4.0) * 70.0
     sampler = {"ms": round(samp_ms, 5), "launches": sum(1 for n in kern_ms if n.startswith("sample_")),

@@ -16,7 +16,7 @@ void set_hip_error(hipError_t e, const char* what) {
 }
 
 static const char* const kKernelNames[KID_COUNT] = {
-    "sample_mark",  "sample_hist0", "sample_hist1", "sample_hist2", "sample_count",
+    "sample_hist0", "sample_hist1", "sample_hist2", "sample_count",
     "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_rowmax",
     "row_ref", "gemm_logits",
     "row_combine",   "gemm_dweight", "dweight_reduce", "dweight_label",

@@ -20,8 +20,7 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 // Kernel ids for the optional per-kernel timing.
 enum KernelId {
-  KID_SAMPLE_MARK = 0,
-  KID_SAMPLE_HIST0,
+  KID_SAMPLE_HIST0 = 0,
   KID_SAMPLE_HIST1,
   KID_SAMPLE_HIST2,
   KID_SAMPLE_COUNT,

@@ -61,19 +61,8 @@ __device__ __forceinline__ uint32_t pos_nibble(const uint32_t* __restrict__ pos_
 // Between two calls the sampler's scratch is all zero (bitmap, histograms, counter of positives):
 // pfc_create clears it once, and the last reader of each piece clears it again -- the scan of a
 // pass its histogram, the first scan the counter, the label remap the bitmap words it knows to be
-// set -- so no call starts with a clearing pass.
-
-__global__ void sample_mark_kernel(const int64_t* __restrict__ labels, int B, int64_t N,
-                                   uint32_t* __restrict__ pos_bits, int32_t* __restrict__ err_flag) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= B) return;
-  const int64_t y = labels[i];
-  if (y < 0 || y >= N) {
-    atomicOr(err_flag, 1);
-    return;
-  }
-  atomicOr(&pos_bits[y >> 5], 1u << (y & 31));
-}
+// set -- so no call starts with a clearing pass.  The batch classes are marked inside the launch
+// of the first radix pass (see sample_hist_kernel), not by a launch of their own.
 
 // All 256 threads of a workgroup: walk the merged histogram of pass P from the largest bin
 // downwards until `need` classes are covered.  Returns (to every thread) the bin that holds the
@@ -173,28 +162,52 @@ __device__ __forceinline__ void select_state(uint32_t* __restrict__ hist, SelSta
   }
 }
 
-// Radix pass P over the non-positive classes whose score agrees with the prefix found so far;
-// pass 0 also counts the positives.
+// Radix pass P over the classes whose score agrees with the prefix found so far.
+// Passes 1 and 2 skip the classes of the batch (their bits are complete by then).  Pass 0 runs in
+// the same launch as the marking of the batch classes, so it cannot know them yet: it counts EVERY
+// class, and the workgroups behind the first `hist_blocks` mark the labels -- the one thread that
+// sets a class's bit first takes that class's score out of the merged histogram again and counts
+// the class as a positive.  Integer atomics only, so the histogram after the launch is the same
+// whatever the order.
 template <int P>
-__global__ void sample_hist_kernel(int64_t N, PhiloxKey key, const uint32_t* __restrict__ pos_bits,
+__global__ void sample_hist_kernel(int64_t N, PhiloxKey key, uint32_t* __restrict__ pos_bits,
                                    uint32_t* __restrict__ hist, SelState* __restrict__ sel,
-                                   uint32_t ceil_rN) {
+                                   uint32_t ceil_rN, const int64_t* __restrict__ labels, int B,
+                                   int hist_blocks, int32_t* __restrict__ err_flag) {
   constexpr int kBins = Pass<P>::kBins, kShift = Pass<P>::kShift;
+  if constexpr (P == 0) {
+    if ((int)blockIdx.x >= hist_blocks) {   // marking part of the launch
+      const int i = ((int)blockIdx.x - hist_blocks) * kThreads + threadIdx.x;
+      if (i >= B) return;
+      const int64_t y = labels[i];
+      if (y < 0 || y >= N) {
+        atomicOr(err_flag, 1);
+        return;
+      }
+      const uint32_t bit = 1u << (y & 31);
+      const uint32_t old = atomicOr(&pos_bits[y >> 5], bit);
+      if (!(old & bit)) {   // first to mark class y
+        uint32_t u[4];
+        philox_block((uint32_t)(y >> 2), key, u);
+        atomicSub(&hist[u[y & 3] >> kShift], 1u);
+        atomicAdd(&sel->U, 1u);
+      }
+      return;
+    }
+  }
   __shared__ uint32_t lh[kBins];
-  __shared__ uint32_t lpos;
   for (int b = threadIdx.x; b < kBins; b += blockDim.x) lh[b] = 0u;
-  if (threadIdx.x == 0) lpos = 0u;
   uint32_t prefix = 0u, need = 0u, none = 0u;
   if constexpr (P > 0) select_state<P>(hist, sel, ceil_rN, prefix, need, none);
   __syncthreads();
   if (!(P > 0 && none)) {
     const uint32_t nq = (uint32_t)((N + 3) >> 2);
-    uint32_t npos = 0;
-    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < nq; q += gridDim.x * blockDim.x) {
+    const uint32_t stride = (uint32_t)hist_blocks * blockDim.x;
+    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < nq; q += stride) {
       uint32_t u[4];
       philox_block(q, key, u);
-      const uint32_t pb = pos_nibble(pos_bits, q);
-      if (P == 0) npos += __popc(pb);
+      uint32_t pb = 0u;
+      if constexpr (P > 0) pb = pos_nibble(pos_bits, q);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int64_t j = (int64_t)q * 4 + e;
@@ -209,14 +222,12 @@ __global__ void sample_hist_kernel(int64_t N, PhiloxKey key, const uint32_t* __r
         }
       }
     }
-    if (P == 0 && npos) atomicAdd(&lpos, npos);
   }
   __syncthreads();
   for (int b = threadIdx.x; b < kBins; b += blockDim.x) {
     const uint32_t c = lh[b];
     if (c) atomicAdd(&hist[P * kHistStride + b], c);
   }
-  if (P == 0 && threadIdx.x == 0 && lpos) atomicAdd(&sel->U, lpos);
 }
 
 // Selection predicate pieces for classes 4q..4q+3: bit e of `sure` = positive or score above the
@@ -395,14 +406,14 @@ int sample_impl(pfc_ctx* c, const int64_t* labels, int32_t B, double r, uint64_t
   if (hist_blocks > 512) hist_blocks = 512;
   if (hist_blocks < 1) hist_blocks = 1;
 
-  PFC_LAUNCH(c, KID_SAMPLE_MARK, sample_mark_kernel, dim3((B + kThreads - 1) / kThreads),
-             dim3(kThreads), 0, labels, B, N, c->pos_bits, c->err_flag);
-  PFC_LAUNCH(c, KID_SAMPLE_HIST0, sample_hist_kernel<0>, dim3(hist_blocks), dim3(kThreads), 0, N,
-             key, c->pos_bits, c->hist, c->sel, (uint32_t)crn);
+  const int mark_blocks = (B + kThreads - 1) / kThreads;
+  PFC_LAUNCH(c, KID_SAMPLE_HIST0, sample_hist_kernel<0>, dim3(hist_blocks + mark_blocks),
+             dim3(kThreads), 0, N, key, c->pos_bits, c->hist, c->sel, (uint32_t)crn, labels, B,
+             hist_blocks, c->err_flag);
   PFC_LAUNCH(c, KID_SAMPLE_HIST1, sample_hist_kernel<1>, dim3(hist_blocks), dim3(kThreads), 0, N,
-             key, c->pos_bits, c->hist, c->sel, (uint32_t)crn);
+             key, c->pos_bits, c->hist, c->sel, (uint32_t)crn, labels, B, hist_blocks, c->err_flag);
   PFC_LAUNCH(c, KID_SAMPLE_HIST2, sample_hist_kernel<2>, dim3(hist_blocks), dim3(kThreads), 0, N,
-             key, c->pos_bits, c->hist, c->sel, (uint32_t)crn);
+             key, c->pos_bits, c->hist, c->sel, (uint32_t)crn, labels, B, hist_blocks, c->err_flag);
   PFC_LAUNCH(c, KID_SAMPLE_COUNT, sample_count_kernel, dim3(nblk), dim3(kThreads), 0, N, key,
              c->pos_bits, c->hist, c->sel, (uint32_t)crn, c->blk_cnt);
   PFC_LAUNCH(c, KID_SAMPLE_WRITE, sample_write_kernel, dim3(nblk), dim3(kThreads), 0, N, key,
