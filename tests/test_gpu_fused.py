@@ -36,6 +36,8 @@ CASES = [
     (10_000, 128, 512, 0.1, binding.PRECISION_FP32, 10_000),    # too few tiles
     (93_431, 512, 512, 0.1, binding.PRECISION_BF16, 93_431),
     (3_000, 100, 256, 0.1, binding.PRECISION_FP32, 3_000),      # D != 512
+    (5_000, 70, 1024, 0.2, binding.PRECISION_BF16, 5_000),      # D = 1024
+    (4_000, 33, 768, 0.15, binding.PRECISION_FP32, 40),         # D = 768, duplicates
     (50_000, 4096, 512, 1e-9, binding.PRECISION_BF16, 50_000),  # k = U small, batch sliced
 ]
 
@@ -104,6 +106,57 @@ def test_fused_equals_two_calls(N, B, D, r, precision, spread, options):
     rv, nv = row_rel_max(vb[sel], va[sel])
     _say("   v per-row diff fused vs two calls", rv)
     assert rv <= 1e-4 and nv >= 0.9 * sel.size
+
+
+@pytest.mark.parametrize("precision", [binding.PRECISION_FP32, binding.PRECISION_BF16])
+def test_fused_at_a_scale_above_64(precision):
+    """The fused call with the softmax relative to each sample's largest logit (s = 128), one-kernel
+    form: same bits as the two calls for loss and feature gradient, centers and momentum equal
+    up to the summation order, and the loss inside the bar against the oracle."""
+    torch = _torch()
+    N, B, D, r, s, m, lr, mu = 400_000, 200, 512, 0.1, 128.0, 0.5, 0.1, 0.9
+    rng = np.random.default_rng(91)
+    W0 = (rng.standard_normal((N, D)) * 0.01).astype(np.float32)
+    X = rng.standard_normal((B, D)).astype(np.float32)
+    labels = rng.integers(0, N, size=B).astype(np.int64)
+    out = {}
+    for fused in (False, True):
+        _say("fused at s = 128", precision, "fused" if fused else "split")
+        ctx = binding.Context(N, D, B, r, precision)
+        Wd = torch.from_numpy(W0).cuda()
+        vd = torch.zeros_like(Wd)
+        cap = binding.pfc_num_sampled(N, B, r)
+        idx = torch.zeros(cap, dtype=torch.int32, device="cuda")
+        yl = torch.zeros(B, dtype=torch.int32, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        dX = torch.zeros(B, D, device="cuda")
+        Xd, ld = torch.from_numpy(X).cuda(), torch.from_numpy(labels).cuda()
+        k = ctx.pfc_sample(ld, r, 0, 0, idx, yl)
+        if fused:
+            ctx.pfc_forward_backward_update(Xd, Wd, vd, idx, k, yl, s, m, lr, mu, loss, dX)
+        else:
+            dW = torch.zeros(cap, D, device="cuda")
+            ctx.pfc_forward_backward(Xd, Wd, idx, k, yl, s, m, loss, dX, dW)
+            ctx.pfc_update(Wd, vd, idx, k, dW, lr, mu)
+        torch.cuda.synchronize()
+        assert ctx.pfc_check() == binding.PFC_OK
+        out[fused] = (Wd.cpu().numpy(), vd.cpu().numpy(), float(loss.item()), dX.cpu().numpy(),
+                      idx[:k].cpu().numpy(), yl.cpu().numpy())
+        ctx.close()
+    Wa, va, la, dXa, ia, ya = out[False]
+    Wb, vb, lb, dXb, ib, yb = out[True]
+    assert la == lb and dXa.tobytes() == dXb.tobytes() and np.array_equal(ia, ib)
+    sel = ia.astype(np.int64)
+    nrm = np.linalg.norm(Wa[sel].astype(np.float64), axis=1)
+    assert row_rel_err(Wb[sel], Wa[sel], nrm) <= 1e-6
+    assert rel_max(vb[sel], va[sel]) <= 1e-5
+    o = O.forward_backward(X, W0[sel], ya, s, m)
+    assert abs(lb - o["loss"]) <= LOSS_TOL[precision] * abs(o["loss"]), (lb, o["loss"])
+    W64, v64 = W0.astype(np.float64), np.zeros((N, D))
+    O.update(W64, v64, sel, o["dW"], lr, mu)
+    err = row_rel_err(Wb[sel], W64[sel], np.linalg.norm(W64[sel], axis=1))
+    _say("   loss", lb, o["loss"], "W row err", err)
+    assert err <= W_TOL * 2      # the logit error, and with it the step of a center, doubles with s
 
 
 def test_fused_tiny_workload_step():
