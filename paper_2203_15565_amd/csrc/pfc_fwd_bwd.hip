@@ -282,7 +282,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
     const typename Cfg::elem* __restrict__ Wn, const typename Cfg::elem* __restrict__ Xn, int D,
     int64_t k, int B, int Bp, int64_t kp, const int32_t* __restrict__ yl, LossParams lp,
     typename Cfg::elem* __restrict__ E, float* __restrict__ rowpart,
-    float* __restrict__ rowmaxpart, float* __restrict__ clabel, int tiles_j, int tiles_i) {
+    float* __restrict__ rowmaxpart, float* __restrict__ clabel, int tiles_j, int tiles_i,
+    int ahead) {
   using T = typename Cfg::elem;
   extern __shared__ __align__(16) char smem[];
   int tj, ti;
@@ -295,6 +296,23 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
   PFC_PHASE(1, 0);
   gemm_tile<Cfg>(Wn + j0 * D, D, Xn + (int64_t)i0 * D, D, D / Cfg::BK, smem, acc);
   PFC_PHASE(1, 1);
+  // Pull the Wn block of the class tile that the workgroups `ahead` ids later will multiply (same
+  // XCD, about one round later) into this XCD's L2: the tiles_i workgroups of a class tile touch
+  // a part of the rows each, one 4-byte load per 128-byte line.  The values are only kept alive
+  // until the end of the kernel, never used.
+  uint32_t touched = 0;
+  {
+    int ntj, nti;
+    const int nb = (int)blockIdx.x + ahead;
+    if (nb < (int)gridDim.x && xcd_tile(nb, tiles_i, tiles_j, ntj, nti)) {
+      const int row_bytes = D * (int)sizeof(T);
+      const int off = ((nti * 256) % row_bytes) + (threadIdx.x & 1) * 128;
+      const char* p = reinterpret_cast<const char*>(Wn + (int64_t)ntj * Cfg::BM * D) +
+                      (int64_t)(threadIdx.x >> 1) * row_bytes + off;
+      touched = *reinterpret_cast<const uint32_t*>(p);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
 
   constexpr bool kStage = (sizeof(T) == 2);          // bf16: transpose the tile through LDS
   constexpr int SX = Cfg::BM * 2 + 8;                // staging row (one sample) stride in bytes
@@ -370,6 +388,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
     }
   }
   PFC_PHASE(1, 3);
+  asm volatile("" ::"v"(touched));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1045,7 +1064,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     auto logits_kernel = lp.extras ? gemm_logits_kernel<CfgF, true> : gemm_logits_kernel<CfgF, false>;
     PFC_LAUNCH(c, KID_GEMM_LOGITS, logits_kernel, dim3(xcd_grid(tiles_i, tiles_j)),
                dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, Bp, kp, yl, lp, E, c->rowpart,
-               c->rowmaxpart, c->clabel, tiles_j, tiles_i);
+               c->rowmaxpart, c->clabel, tiles_j, tiles_i, c->num_cu / 8 * 8);
     auto combine_kernel = row_combine_kernel<T, NC>;
     PFC_LAUNCH(c, KID_ROW_COMBINE, combine_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowpart,
                tiles_j, B, Bp, D, X, c->rnormX, c->clabel, lp, c->rowmaxpart, c->rowscale,
