@@ -38,8 +38,10 @@ extern "C" {
 typedef struct pfc_ctx pfc_ctx;
 
 /* Create a context holding the scratch for problems up to (N classes, D, B_max samples, ratio
- * r_max).  D must be a multiple of 256 and at most 1024; 1 <= N < 2^31; 0 < r_max <= 1; the
- * largest sampled set, pfc_num_sampled(N, B_max, r_max), must stay below 2^25 classes (bf16
+ * r_max).  D must be a multiple of 64, 64 <= D <= 1024 (the GEMMs work on rows padded to the next
+ * multiple of 256 inside the library: D = 256, 512, 768, 1024 waste nothing; the one-kernel form
+ * of pfc_forward_backward_update exists for D = 512, other D take its two-kernel form);
+ * 1 <= N < 2^31; 0 < r_max <= 1; the largest sampled set, pfc_num_sampled(N, B_max, r_max), must stay below 2^25 classes (bf16
  * operands) or 2^24 (fp32 operands): PFC_EINVAL otherwise.
  * `hip_stream` is a hipStream_t (NULL = the default stream).  Allocates device memory. */
 int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,

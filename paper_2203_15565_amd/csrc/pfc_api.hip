@@ -86,7 +86,7 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   if (!out) return PFC_EINVAL;
   *out = nullptr;
   if (N < 1 || N >= (int64_t)1 << 31) return PFC_EINVAL;
-  if (D < 256 || D > 1024 || D % 256 != 0) return PFC_EINVAL;
+  if (D < 64 || D > 1024 || D % 64 != 0) return PFC_EINVAL;
   if (B_max < 1 || B_max > (1 << 20)) return PFC_EINVAL;
   if (!(r_max > 0.0) || !(r_max <= 1.0)) return PFC_EINVAL;
   if (precision != PFC_PRECISION_FP32 && precision != PFC_PRECISION_BF16) return PFC_EINVAL;
@@ -121,6 +121,7 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
 
   const size_t es = c->esize;
   const size_t Bp = (size_t)c->Bp_cap, kp = (size_t)c->kp_cap, Dz = (size_t)D;
+  const size_t Dpz = (size_t)round_up(D, 256);   // row length of the GEMM operands
   c->nblk_cap = (int32_t)((N + 2047) / 2048);
   int rc = PFC_OK;
 #define ALLOC(field, bytes)                                  \
@@ -130,10 +131,10 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(sel, sizeof(SelState));
   ALLOC(blk_cnt, (size_t)c->nblk_cap * 2 * 4);
   ALLOC(err_flag, 16);
-  ALLOC(Xn, Bp * Dz * es);
-  ALLOC(Xs, Bp * Dz * es);
+  ALLOC(Xn, Bp * Dpz * es);
+  ALLOC(Xs, Bp * Dpz * es);
   ALLOC(rnormX, Bp * 4);
-  ALLOC(Wn, kp * Dz * es);
+  ALLOC(Wn, kp * Dpz * es);
   ALLOC(rnormW, kp * 4);
   ALLOC(head, kp * 4);
   ALLOC(E, Bp * kp * es);
@@ -145,7 +146,7 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(rowscale, Bp * 4);
   ALLOC(dlabel, Bp * 4);
   ALLOC(lossrow, Bp * 4);
-  ALLOC(dXpart, (size_t)kMaxSplits * Bp * Dz * 4);
+  ALLOC(dXpart, (size_t)kMaxSplits * Bp * Dpz * 4);
   ALLOC(dlab, Bp * Dz * 4);
   ALLOC(dWtmp, (size_t)c->k_cap * Dz * 4);
   ALLOC(spare, 2 * Dz * 4);

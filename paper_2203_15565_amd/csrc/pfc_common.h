@@ -78,10 +78,10 @@ struct pfc_ctx {
   uint32_t* host_pin;     // pinned host words for read-backs
 
   // forward/backward scratch (T = float or bf16 according to precision)
-  void* Xn;        // [Bp x D]   normalised features
-  void* Xs;        // [Bp x D]   (s/(B*l_i)) * xn_i
+  void* Xn;        // [Bp x Dp]  normalised features (Dp = D rounded up to 256, zero columns)
+  void* Xs;        // [Bp x Dp]  (s/(B*l_i)) * xn_i
   float* rnormX;   // [Bp]
-  void* Wn;        // [kp x D]   normalised sampled centers
+  void* Wn;        // [kp x Dp]  normalised sampled centers
   float* rnormW;   // [kp]
   int32_t* head;   // [kp] first sample of the batch that carries class idx[j], else INT_MAX
   void* E;         // [Bp x kp]  exp(z), label column zeroed
@@ -93,7 +93,7 @@ struct pfc_ctx {
   float* rowscale; // [Bp] s/(B*l_i)
   float* dlabel;   // [Bp] (s/B)(p_iy - 1) rho_i
   float* lossrow;  // [Bp]
-  float* dXpart;   // [splits x Bp x D]
+  float* dXpart;   // [splits x Bp x Dp]
   float* dlab;     // [Bp x D] label-column part of dWn, one row per first sample of a class (fused step)
   float* dWtmp;    // [k_cap x D] dWn of the fused step whenever its one-kernel form does not apply
   float* spare;    // [2 x D] a row of zeros (never written) and a row that only takes the stores of

@@ -21,6 +21,8 @@
 #include <limits.h>
 #include <math.h>
 
+#include <type_traits>
+
 #include "pfc_common.h"
 #include "pfc_gemm.h"
 
@@ -57,6 +59,11 @@ constexpr float kEpsSin2 = 1e-12f;
 
 // ---------------------------------------------------------------------------------------------
 // normalize_x: one wavefront per (padded) feature row.
+//
+// Row length: the caller's arrays (X, W, v, dX, dWn) have rows of D floats, D a multiple of 64.
+// The library's own GEMM operands (Xn, Xs, Wn and the dfeatures partial sums) have rows of
+// Dp = 256 * NC >= D elements, the columns from D on being zero, so that the GEMMs only ever
+// see whole 256-column tiles; kernels that touch the caller's rows skip the columns from D on.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int NC>
 __global__ void normalize_x_kernel(const float* __restrict__ X, int B, int Bp, int D,
@@ -66,29 +73,26 @@ __global__ void normalize_x_kernel(const float* __restrict__ X, int B, int Bp, i
   const int lane = threadIdx.x & 63;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (i >= Bp) return;
-  constexpr int nchunk = NC;   // float4 chunks per lane (D = 256 * NC)
+  constexpr int nchunk = NC;   // float4 chunks per lane
+  constexpr int Dp = 256 * NC;
   float4 v[NC];
   float ss = 0.f;
-  if (i < B) {
 #pragma unroll
-    for (int c = 0; c < nchunk; ++c) {
-      v[c] = *reinterpret_cast<const float4*>(X + (int64_t)i * D + c * 256 + lane * 4);
-      ss += v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
-    }
+  for (int c = 0; c < nchunk; ++c) {
+    const int d = c * 256 + lane * 4;
+    v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < B && d < D) v[c] = *reinterpret_cast<const float4*>(X + (int64_t)i * D + d);
+    ss += v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
   }
   ss = wave_sum(ss);
   const float rn = (i < B) ? 1.f / fmaxf(sqrtf(ss), kEpsNorm) : 0.f;
 #pragma unroll
   for (int c = 0; c < nchunk; ++c) {
-    T* dst = Xn + (int64_t)i * D + c * 256 + lane * 4;
-    if (i < B) {
-      dst[0] = from_float<T>(v[c].x * rn);
-      dst[1] = from_float<T>(v[c].y * rn);
-      dst[2] = from_float<T>(v[c].z * rn);
-      dst[3] = from_float<T>(v[c].w * rn);
-    } else {
-      dst[0] = dst[1] = dst[2] = dst[3] = from_float<T>(0.f);
-    }
+    T* dst = Xn + (int64_t)i * Dp + c * 256 + lane * 4;   // rn == 0 for padded rows
+    dst[0] = from_float<T>(v[c].x * rn);
+    dst[1] = from_float<T>(v[c].y * rn);
+    dst[2] = from_float<T>(v[c].z * rn);
+    dst[3] = from_float<T>(v[c].w * rn);
   }
   if (lane == 0) {
     rnormX[i] = rn;
@@ -112,6 +116,7 @@ __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N
                                           int32_t* __restrict__ head,
                                           int32_t* __restrict__ err_flag) {
   constexpr int NB = 4;
+  constexpr int Dp = 256 * NC;
   const int lane = threadIdx.x & 63;
   const int64_t jb = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * NB;
   if (jb >= kp) return;
@@ -127,13 +132,16 @@ __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N
       if (!ok[u] && lane == 0) atomicOr(err_flag, 4);
       if (ok[u]) {
 #pragma unroll
-        for (int c = 0; c < NC; ++c)
-        {
+        for (int c = 0; c < NC; ++c) {
           // streamed once: a nontemporal load keeps these rows from displacing what the GEMMs
           // that follow want in the L2 (measured: 0.145 -> 0.121 ms at the headline workload)
-          const f32x4 t = __builtin_nontemporal_load(
-              reinterpret_cast<const f32x4*>(W + row * D + c * 256 + lane * 4));
-          v[u][c] = make_float4(t[0], t[1], t[2], t[3]);
+          const int d = c * 256 + lane * 4;
+          v[u][c] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (d < D) {
+            const f32x4 t =
+                __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(W + row * D + d));
+            v[u][c] = make_float4(t[0], t[1], t[2], t[3]);
+          }
         }
       }
     }
@@ -166,7 +174,7 @@ __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N
       } else {
         o[0] = o[1] = o[2] = o[3] = from_float<T>(0.f);
       }
-      T* g = Wn + j * D + c * 256 + lane * 4;
+      T* g = Wn + j * Dp + c * 256 + lane * 4;
       if constexpr (sizeof(T) == 2) {
         uint2 pk;
         __builtin_memcpy(&pk, o, 8);
@@ -515,17 +523,17 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
   for (int c = 0; c < NC; ++c) {
     const int d = c * 256 + lane * 4;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < B) v = *reinterpret_cast<const float4*>(X + (int64_t)i * D + d);
+    if (i < B && d < D) v = *reinterpret_cast<const float4*>(X + (int64_t)i * D + d);
     T o[4] = {from_float<T>(v.x * f), from_float<T>(v.y * f), from_float<T>(v.z * f),
               from_float<T>(v.w * f)};
     if constexpr (sizeof(T) == 2) {
       uint2 pk;
       __builtin_memcpy(&pk, o, 8);
-      *reinterpret_cast<uint2*>(Xs + (int64_t)i * D + d) = pk;
+      *reinterpret_cast<uint2*>(Xs + (int64_t)i * (256 * NC) + d) = pk;
     } else {
       uint4 pk;
       __builtin_memcpy(&pk, o, 16);
-      *reinterpret_cast<uint4*>(Xs + (int64_t)i * D + d) = pk;
+      *reinterpret_cast<uint4*>(Xs + (int64_t)i * (256 * NC) + d) = pk;
     }
   }
 }
@@ -534,12 +542,13 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
 // gemm_dweight: dWn[j][d] = sum_i E[i][j] * Xs[i][d] (both operands k-major); rows j < k are
 // written.  When k is small and the batch large (the regime without extra negatives, Sec. 3.3)
 // there are too few tiles to fill the GPU: SPLIT cuts the batch (the reduction) into slices that
-// write partial tiles, summed in fixed order by dweight_reduce.
+// write partial tiles, summed in fixed order by dweight_reduce.  Xs has rows of Dp elements; the
+// partial tiles too; dWn (the caller's) has rows of D floats, columns from D on are not stored.
 // ---------------------------------------------------------------------------------------------
 template <class Cfg, bool SPLIT>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_kernel(
     const typename Cfg::elem* __restrict__ E, const typename Cfg::elem* __restrict__ Xs, int D,
-    int64_t k, int64_t kp, int Bp, float* __restrict__ out, int tiles_j, int tiles_d,
+    int Dp, int64_t k, int64_t kp, int Bp, float* __restrict__ out, int tiles_j, int tiles_d,
     int slabs_per, int splits) {
   extern __shared__ __align__(16) char smem[];
   int tj, td, sp = 0, ns = Bp / Cfg::BK;
@@ -559,31 +568,46 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_dweight_kernel(
   f32x16 acc[Cfg::TM][Cfg::TN];
   zero_acc<Cfg>(acc);
   PFC_PHASE(2, 0);
-  gemm_tile<Cfg>(E + i0 * kp + j0, kp, Xs + i0 * D + d0, D, ns, smem, acc);
+  gemm_tile<Cfg>(E + i0 * kp + j0, kp, Xs + i0 * Dp + d0, Dp, ns, smem, acc);
   PFC_PHASE(2, 1);
-  float* dst = SPLIT ? out + (int64_t)sp * kp * D : out;
+  float* dst = SPLIT ? out + (int64_t)sp * kp * Dp : out;
+  const int ld = SPLIT ? Dp : D;
+  auto store_tile = [&](auto guarded) {
+    bool col_in[Cfg::TN];
 #pragma unroll
-  for (int bm = 0; bm < Cfg::TM; ++bm)
+    for (int bn = 0; bn < Cfg::TN; ++bn) col_in[bn] = !guarded.value || d0 + acc_col<Cfg>(bn) < D;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int64_t j = j0 + acc_row<Cfg>(bm, r);
-      if (SPLIT || j < k) {
+    for (int bm = 0; bm < Cfg::TM; ++bm)
 #pragma unroll
-        for (int bn = 0; bn < Cfg::TN; ++bn)
-          dst[j * D + d0 + acc_col<Cfg>(bn)] = acc[bm][bn][r];
+      for (int r = 0; r < 16; ++r) {
+        const int64_t j = j0 + acc_row<Cfg>(bm, r);
+        if (SPLIT || j < k) {
+#pragma unroll
+          for (int bn = 0; bn < Cfg::TN; ++bn)
+            if (col_in[bn]) dst[j * ld + d0 + acc_col<Cfg>(bn)] = acc[bm][bn][r];
+        }
       }
-    }
+  };
+  // only the last column tile of a D that is no multiple of the tile width needs the guard
+  if (SPLIT || d0 + Cfg::BN <= D)
+    store_tile(std::false_type{});
+  else
+    store_tile(std::true_type{});
   PFC_PHASE(2, 2);
 }
 
-// dW[j][d] = sum over slices of part[slice][j][d], in slice order.
+// dW[j][d] = sum over slices of part[slice][j][d], in slice order (rows of Dp floats in `part`, of
+// D floats in dW).
 __global__ void dweight_reduce_kernel(const float* __restrict__ part, int splits, int64_t k,
-                                      int64_t kp, int D, float* __restrict__ dW) {
+                                      int64_t kp, int D, int Dp, float* __restrict__ dW) {
   const int64_t e4 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e4 >= k * D / 4) return;
+  const int64_t j = e4 / (D / 4);
+  const int d = (int)(e4 - j * (D / 4)) * 4;
   float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int sp = 0; sp < splits; ++sp) {
-    const float4 t = *reinterpret_cast<const float4*>(part + (int64_t)sp * kp * D + e4 * 4);
+    const float4 t =
+        *reinterpret_cast<const float4*>(part + ((int64_t)sp * kp + j) * Dp + d);
     a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
   }
   *reinterpret_cast<float4*>(dW + e4 * 4) = a;
@@ -923,6 +947,7 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
   const int i = blockIdx.x;
   const int wave = threadIdx.x >> 6;
   constexpr int nchunk = NC;
+  constexpr int Dp = 256 * NC;   // row length of the partial sums
   __shared__ float4 s_part[3][NC][64];
   float4 sum[NC];
 #pragma unroll
@@ -930,7 +955,7 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
   for (int sp = wave; sp < splits; sp += 4) {
 #pragma unroll
     for (int c = 0; c < nchunk; ++c) {
-      const float4 t = *reinterpret_cast<const float4*>(part + ((int64_t)sp * Bp + i) * D +
+      const float4 t = *reinterpret_cast<const float4*>(part + ((int64_t)sp * Bp + i) * Dp +
                                                         c * 256 + lane * 4);
       sum[c].x += t.x; sum[c].y += t.y; sum[c].z += t.z; sum[c].w += t.w;
     }
@@ -965,12 +990,13 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
     const int d = c * 256 + lane * 4;
     float4 a = sum[c];
     a.x *= rs; a.y *= rs; a.z *= rs; a.w *= rs;
-    if (wrow >= 0) {
+    if (wrow >= 0 && d < D) {
       const float4 w = *reinterpret_cast<const float4*>(W + wrow * D + d);
       const float f = dl * rnw;
       a.x += f * w.x; a.y += f * w.y; a.z += f * w.z; a.w += f * w.w;
     }
-    float4 x = *reinterpret_cast<const float4*>(X + (int64_t)i * D + d);
+    float4 x = make_float4(0.f, 0.f, 0.f, 0.f);   // partial sums and x are zero from column D on
+    if (d < D) x = *reinterpret_cast<const float4*>(X + (int64_t)i * D + d);
     x.x *= rnx; x.y *= rnx; x.z *= rnx; x.w *= rnx;
     g[c] = a;
     xn[c] = x;
@@ -984,7 +1010,8 @@ __global__ void dfeatures_final_kernel(const float* __restrict__ part, int split
     o.y = (g[c].y - u * xn[c].y) * rnx;
     o.z = (g[c].z - u * xn[c].z) * rnx;
     o.w = (g[c].w - u * xn[c].w) * rnx;
-    *reinterpret_cast<float4*>(dX + (int64_t)i * D + c * 256 + lane * 4) = o;
+    if (c * 256 + lane * 4 < D)
+      *reinterpret_cast<float4*>(dX + (int64_t)i * D + c * 256 + lane * 4) = o;
   }
 }
 
@@ -1019,6 +1046,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                                 ? FusedUpdateLds<CfgU>::LDS : FusedUpdateLds<CfgUS>::LDS;
   static_assert(kFusedLds <= 160 * 1024, "LDS of one compute unit");
   const int D = c->D;
+  constexpr int Dp = 256 * NC;   // row length of the library's own GEMM operands
   const int Bp = (int)round_up(B, kPadB);
   const int64_t kp = round_up(k, kPadK);
   T* Xn = (T*)c->Xn; T* Xs = (T*)c->Xs; T* Wn = (T*)c->Wn; T* E = (T*)c->E;
@@ -1054,7 +1082,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     const int tiles_j = (int)(kp / CfgF::BM), tiles_i = Bp / CfgF::BN;
     if (lp.rowref) {   // scale above 64: the largest logit of every sample first
       PFC_LAUNCH(c, KID_GEMM_ROWMAX, gemm_rowmax_kernel<CfgF>, dim3(xcd_grid(tiles_i, tiles_j)),
-                 dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, yl, lp, c->rowmaxpart,
+                 dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, Dp, k, B, yl, lp, c->rowmaxpart,
                  tiles_j, tiles_i);
       PFC_LAUNCH(c, KID_ROW_REF, row_ref_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowmaxpart,
                  tiles_j, B, Bp, c->rowref);
@@ -1063,7 +1091,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     // stays lean
     auto logits_kernel = lp.extras ? gemm_logits_kernel<CfgF, true> : gemm_logits_kernel<CfgF, false>;
     PFC_LAUNCH(c, KID_GEMM_LOGITS, logits_kernel, dim3(xcd_grid(tiles_i, tiles_j)),
-               dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, D, k, B, Bp, kp, yl, lp, E, c->rowpart,
+               dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, Dp, k, B, Bp, kp, yl, lp, E, c->rowpart,
                c->rowmaxpart, c->clabel, tiles_j, tiles_i, c->num_cu / 8 * 8);
     auto combine_kernel = row_combine_kernel<T, NC>;
     PFC_LAUNCH(c, KID_ROW_COMBINE, combine_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowpart,
@@ -1072,7 +1100,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   }
   // dweight (+ label part) into dW_out
   auto launch_dweight = [&]() -> int {
-    const int tiles_j = (int)(kp / CfgW::BM), tiles_d = D / CfgW::BN;
+    const int tiles_j = (int)(kp / CfgW::BM), tiles_d = Dp / CfgW::BN;
     const int slabs_total = Bp / CfgW::BK;
     // slices of the batch when the tiles alone leave most CUs idle; the partial tiles borrow the
     // dfeatures split buffer, which is not in use at that point
@@ -1082,14 +1110,14 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
       const int nsp = (slabs_total + slabs_per - 1) / slabs_per;
       PFC_LAUNCH(c, KID_GEMM_DW, (gemm_dweight_kernel<CfgW, true>),
                  dim3(xcd_grid(tiles_j * tiles_d, nsp)), dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs,
-                 D, k, kp, Bp, c->dXpart, tiles_j, tiles_d, slabs_per, nsp);
+                 D, Dp, k, kp, Bp, c->dXpart, tiles_j, tiles_d, slabs_per, nsp);
       PFC_LAUNCH(c, KID_DW_REDUCE, dweight_reduce_kernel,
                  dim3((unsigned)((k * D / 4 + 255) / 256)), dim3(256), 0, c->dXpart, nsp, k, kp, D,
-                 dW_out);
+                 Dp, dW_out);
     } else {
       PFC_LAUNCH(c, KID_GEMM_DW, (gemm_dweight_kernel<CfgW, false>),
-                 dim3(xcd_grid(tiles_d, tiles_j)), dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs, D, k,
-                 kp, Bp, dW_out, tiles_j, tiles_d, slabs_total, 1);
+                 dim3(xcd_grid(tiles_d, tiles_j)), dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs, D,
+                 Dp, k, kp, Bp, dW_out, tiles_j, tiles_d, slabs_total, 1);
     }
     PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel<false>, dim3(B), dim3(kLabelThreads), 0, X, B,
                D, yl, k, c->head, c->rnormX, c->dlabel, dW_out);
@@ -1097,7 +1125,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   };
   // dfeatures GEMM (split over S) + final reduction, projection, loss
   auto launch_dfeatures = [&]() -> int {
-    const int tiles_i = Bp / CfgX::BM, tiles_d = D / CfgX::BN;
+    const int tiles_i = Bp / CfgX::BM, tiles_d = Dp / CfgX::BN;
     const int slabs_total = (int)(kp / CfgX::BK);
     int want = c->num_cu / (tiles_i * tiles_d);   // one workgroup per compute unit
     if (want < 1) want = 1;
@@ -1107,7 +1135,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     const int splits = (slabs_total + slabs_per - 1) / slabs_per;
     PFC_LAUNCH(c, KID_GEMM_DX, gemm_dfeatures_kernel<CfgX>,
                dim3(xcd_grid(tiles_i * tiles_d, splits)), dim3(CfgX::THREADS), CfgX::LDS_BYTES, E,
-               Wn, D, Bp, kp, slabs_total, slabs_per, splits, c->dXpart, tiles_i, tiles_d);
+               Wn, Dp, Bp, kp, slabs_total, slabs_per, splits, c->dXpart, tiles_i, tiles_d);
     PFC_LAUNCH(c, KID_DX_FINAL, dfeatures_final_kernel<NC>, dim3(B + 1), dim3(256), 0,
                c->dXpart, splits, B, Bp, D, X, W, c->N, idx, yl, k, c->rnormX, c->rnormW,
                c->rowscale, c->dlabel, dX_out, c->lossrow, loss_out, c->clabel, c->rowmax,
@@ -1166,7 +1194,7 @@ int forward_backward_impl(pfc_ctx* c, const float* X, const float* W, const int3
   lp.extras = (filter_threshold < 1.f || stats_out != nullptr || lp.rowref) ? 1 : 0;
 #define PFC_RUN(T, NC) \
   return run<T, NC>(c, X, W, idx, k, yl, B, lp, loss_out, dX_out, dW_out, stats_out, upd)
-  const int nc = c->D / 256;
+  const int nc = (c->D + 255) / 256;
   if (c->precision == PFC_PRECISION_BF16) {
     switch (nc) {
       case 1: PFC_RUN(__bf16, 1);

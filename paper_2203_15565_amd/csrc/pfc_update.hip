@@ -31,11 +31,14 @@ __global__ void update_kernel(float* __restrict__ W, float* __restrict__ V, int6
   f32x4 w[NC], g[NC], v[NC];
   float ww = 0.f, gw = 0.f;
 #pragma unroll
-  for (int c = 0; c < NC; ++c) {   // D = 256 * NC
+  for (int c = 0; c < NC; ++c) {   // 256 * (NC - 1) < D <= 256 * NC, D a multiple of 64
     const int d = c * 256 + lane * 4;
-    w[c] = *reinterpret_cast<const f32x4*>(W + row * D + d);
-    g[c] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(dWn + j * D + d));
-    v[c] = *reinterpret_cast<const f32x4*>(V + row * D + d);
+    w[c] = g[c] = v[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (d < D) {
+      w[c] = *reinterpret_cast<const f32x4*>(W + row * D + d);
+      g[c] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(dWn + j * D + d));
+      v[c] = *reinterpret_cast<const f32x4*>(V + row * D + d);
+    }
     ww += w[c][0] * w[c][0] + w[c][1] * w[c][1] + w[c][2] * w[c][2] + w[c][3] * w[c][3];
     gw += g[c][0] * w[c][0] + g[c][1] * w[c][1] + g[c][2] * w[c][2] + g[c][3] * w[c][3];
   }
@@ -52,8 +55,10 @@ __global__ void update_kernel(float* __restrict__ W, float* __restrict__ V, int6
       vn[e] = mu * v[c][e] + (g[c][e] - t * w[c][e]) * rn;
       wq[e] = w[c][e] - lr * vn[e];
     }
-    __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(V + row * D + d));
-    __builtin_nontemporal_store(wq, reinterpret_cast<f32x4*>(W + row * D + d));
+    if (d < D) {
+      __builtin_nontemporal_store(vn, reinterpret_cast<f32x4*>(V + row * D + d));
+      __builtin_nontemporal_store(wq, reinterpret_cast<f32x4*>(W + row * D + d));
+    }
   }
 }
 
@@ -63,7 +68,7 @@ int update_impl(pfc_ctx* c, float* W, float* v, const int32_t* idx, int64_t k, c
                 float lr, float mu) {
   const int rows_per_block = 4;   // one wavefront per row
   const unsigned grid = (unsigned)((k + rows_per_block - 1) / rows_per_block);
-  switch (c->D / 256) {
+  switch ((c->D + 255) / 256) {
 #define PFC_UPD(NC)                                                                              \
   case NC: {                                                                                     \
     PFC_LAUNCH(c, KID_UPDATE, update_kernel<NC>, dim3(grid), dim3(rows_per_block * 64), 0, W, v, \

@@ -90,7 +90,8 @@ def test_create_rejects_what_the_header_rules_out():
     lib = binding.load()
     h = ctypes.c_void_p()
     bad = [
-        (1000, 300, 64, 0.1, 1),              # D not a multiple of 256
+        (1000, 300, 64, 0.1, 1),              # D not a multiple of 64
+        (1000, 32, 64, 0.1, 1),               # D below 64
         (1000, 1280, 64, 0.1, 1),             # D above 1024
         (0, 512, 64, 0.1, 1), (1 << 31, 512, 64, 0.1, 1),
         (1000, 512, 0, 0.1, 1), (1000, 512, 64, 0.0, 1), (1000, 512, 64, 1.5, 1),
