@@ -19,7 +19,7 @@ static const char* const kKernelNames[KID_COUNT] = {
     "sample_hist0", "sample_hist1", "sample_hist2", "sample_count",
     "sample_write",  "sample_remap", "normalize_x",  "gather_normalize_w", "gemm_rowmax",
     "row_ref", "gemm_logits",
-    "row_combine",   "gemm_dweight", "dweight_reduce", "dweight_label",
+    "row_combine",   "gemm_dweight", "dweight_reduce", "dweight_label", "dweight_label_combine",
     "gemm_dfeatures", "dfeatures_final", "update", "gemm_dweight_update"};
 
 static int64_t ceil_rN(int64_t N, double r) { return (int64_t)ceil(r * (double)N); }
@@ -136,7 +136,13 @@ int pfc_create(pfc_ctx** out, int64_t N, int32_t D, int32_t B_max, double r_max,
   ALLOC(rnormX, Bp * 4);
   ALLOC(Wn, kp * Dpz * es);
   ALLOC(rnormW, kp * 4);
-  ALLOC(head, kp * 4);
+  {
+    // window heads of the label part: for batches above one window, when the table stays small
+    const int64_t nw = (B_max + kLabelWindow - 1) / kLabelWindow;
+    c->label_windows =
+        (nw >= 2 && nw <= kMaxLabelWindows && nw * (int64_t)kp <= ((int64_t)1 << 26)) ? (int32_t)nw : 0;
+  }
+  ALLOC(head, (size_t)(1 + c->label_windows) * kp * 4);
   ALLOC(E, Bp * kp * es);
   ALLOC(rowpart, (kp / kPadK) * 2 * Bp * 4);
   ALLOC(rowmaxpart, (kp / kPadK) * 2 * Bp * 4);

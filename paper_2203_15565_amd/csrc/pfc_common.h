@@ -15,6 +15,8 @@ namespace pfc {
 constexpr int kPadB = 256;   // batch rows are padded to a multiple of this
 constexpr int kPadK = 256;   // sampled rows are padded to a multiple of this
 constexpr int kMaxSplits = 64;
+constexpr int kLabelWindow = 1024;     // samples per window of the label part of dWn
+constexpr int kMaxLabelWindows = 64;   // one lane of a wavefront initialises one window's head
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
@@ -35,6 +37,7 @@ enum KernelId {
   KID_GEMM_DW,
   KID_DW_REDUCE,
   KID_DW_LABEL,
+  KID_DW_LABEL_SUM,
   KID_GEMM_DX,
   KID_DX_FINAL,
   KID_UPDATE,
@@ -83,7 +86,10 @@ struct pfc_ctx {
   float* rnormX;   // [Bp]
   void* Wn;        // [kp x Dp]  normalised sampled centers
   float* rnormW;   // [kp]
-  int32_t* head;   // [kp] first sample of the batch that carries class idx[j], else INT_MAX
+  int32_t* head;   // [(1 + label_windows) x kp] first sample of the batch that carries class
+                   // idx[j], else INT_MAX; then the same for every window of kLabelWindow samples
+                   // (kp = k rounded up to 256 in the call at hand)
+  int32_t label_windows;   // windows the head buffer has room for (0: none, batch in one piece)
   void* E;         // [Bp x kp]  exp(z), label column zeroed
   float* rowpart;  // [Bp x tiles_j] partial row sums of exp(z)
   float* rowmaxpart;  // [Bp x tiles_j] partial row maxima of the non-label cosines (options)

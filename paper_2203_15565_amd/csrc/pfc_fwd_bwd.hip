@@ -113,7 +113,7 @@ template <typename T, int NC>
 __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N,
                                           const int32_t* __restrict__ idx, int64_t k, int64_t kp,
                                           int D, T* __restrict__ Wn, float* __restrict__ rnormW,
-                                          int32_t* __restrict__ head,
+                                          int32_t* __restrict__ head, int nwin,
                                           int32_t* __restrict__ err_flag) {
   constexpr int NB = 4;
   constexpr int Dp = 256 * NC;
@@ -163,6 +163,8 @@ __global__ void gather_normalize_w_kernel(const float* __restrict__ W, int64_t N
       rnormW[j] = rn;
       head[j] = 0x7fffffff;   // first sample carrying this class: filled in by row_combine
     }
+    // likewise the first sample of every window of kLabelWindow samples (large batches only)
+    if (lane < nwin) head[(int64_t)(1 + lane) * kp + j] = 0x7fffffff;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       T o[4];
@@ -480,8 +482,8 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
                                    const float* __restrict__ rowmaxpart,
                                    float* __restrict__ rowscale, float* __restrict__ dlabel,
                                    float* __restrict__ lossrow, float* __restrict__ rowmax,
-                                   const int32_t* __restrict__ yl, int64_t k,
-                                   int32_t* __restrict__ head, T* __restrict__ Xs) {
+                                   const int32_t* __restrict__ yl, int64_t k, int64_t kp,
+                                   int32_t* __restrict__ head, int nwin, T* __restrict__ Xs) {
   const int lane = threadIdx.x & 63;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (i >= Bp) return;
@@ -510,7 +512,16 @@ __global__ void row_combine_kernel(const float* __restrict__ rowpart, int tiles_
       dlabel[i] = (lp.s / (float)B) * (p - 1.f) * rho;
       rowmax[i] = mx;
       const int32_t y = yl[i];
-      if (y >= 0 && (int64_t)y < k) atomicMin(&head[y], i);   // integer: order-independent
+      if (y >= 0 && (int64_t)y < k) {   // integer atomics: order-independent
+        // A frequent class would bring thousands of atomics onto one word: look first (past the
+        // L1, which may hold an old value; a value read too high only costs the atomic)
+        int32_t* h = &head[y];
+        if (__hip_atomic_load(h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > i) atomicMin(h, i);
+        if (nwin) {
+          h = &head[(int64_t)(1 + i / kLabelWindow) * kp + y];
+          if (__hip_atomic_load(h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > i) atomicMin(h, i);
+        }
+      }
     }
   } else if (lane == 0) {
     lossrow[i] = 0.f;
@@ -619,13 +630,22 @@ __global__ void dweight_reduce_kernel(const float* __restrict__ part, int splits
 // matching samples are listed in ascending order; thread group g (one float4 column per thread)
 // sums the matches whose ordinal is congruent to g, and the groups are combined in fixed order,
 // so the result does not depend on timing.
-// COMPACT (fused step): the sum is not added to dWn[y] but written to row i of a B x D side
+// LABEL_COMPACT (fused step): the sum is not added to dWn[y] but written to row i of a B x D side
 // buffer, i being that first sample; the fused GEMM picks it up through head[].
+// LABEL_WINDOW (batches of more than kLabelWindow samples; Sec. 3.3 enlarges the batch to 8K and
+// 16K): with long-tailed labels one class can own a fifth of the batch, and one workgroup cannot
+// read thousands of feature rows quickly (a compute unit draws a small share of the memory
+// bandwidth).  The batch is cut into windows of kLabelWindow samples; block i sums the samples of
+// its class inside its own window if it is the first of them there (`head` then points at that
+// window's heads), and writes the partial sum to row i of the side buffer; dweight_label_combine
+// adds a class's window sums in window order.
 constexpr int kLabelThreads = 1024;
-template <bool COMPACT>
+static_assert(kLabelWindow == kLabelThreads, "a window is scanned in one pass of the workgroup");
+enum LabelMode { LABEL_ADD, LABEL_COMPACT, LABEL_WINDOW };
+template <LabelMode MODE>
 __global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
     const float* __restrict__ X, int B, int D, const int32_t* __restrict__ yl, int64_t k,
-    const int32_t* __restrict__ head, const float* __restrict__ rnormX,
+    const int32_t* __restrict__ head, int64_t kp, const float* __restrict__ rnormX,
     const float* __restrict__ dlabel, float* __restrict__ dW) {
   __shared__ int s_list[kLabelThreads];
   __shared__ float s_coef[kLabelThreads];   // dlabel_p / |x_p| of the listed samples
@@ -635,15 +655,21 @@ __global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
   const int lane = t & 63, wave = t >> 6;
   const int32_t y = yl[i];
   if (y < 0 || (int64_t)y >= k) return;
+  int p_end = B;
+  if constexpr (MODE == LABEL_WINDOW) {
+    const int w = i / kLabelWindow;
+    head += (int64_t)(1 + w) * kp;   // the heads of this window
+    p_end = min(B, (w + 1) * kLabelWindow);
+  }
   if (head[y] != i) return;   // an earlier sample carries this label and does the sum
   const int cols = D >> 2;                 // float4 columns: 64 .. 256
   const int G = kLabelThreads / cols;      // thread groups
   const int col = t % cols, g = t / cols;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   int ordinal0 = 0;                        // matches seen in earlier chunks
-  for (int p0 = i; p0 < B; p0 += kLabelThreads) {
+  for (int p0 = i; p0 < p_end; p0 += kLabelThreads) {
     const int p = p0 + t;
-    const bool hit = (p < B) && (yl[p] == y);
+    const bool hit = (p < p_end) && (yl[p] == y);
     const unsigned long long bal = __ballot(hit);
     const int before = __popcll(bal & ((1ull << lane) - 1ull));
     if (lane == 0) s_wcnt[wave] = __popcll(bal);
@@ -694,7 +720,7 @@ __global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
       const float4 o = s_part[gg * cols + col];
       r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w;
     }
-    if constexpr (COMPACT) {
+    if constexpr (MODE != LABEL_ADD) {
       *reinterpret_cast<float4*>(dW + (int64_t)i * D + col * 4) = r;
     } else {
       float4* dst = reinterpret_cast<float4*>(dW + (int64_t)y * D + col * 4);
@@ -702,6 +728,36 @@ __global__ __launch_bounds__(kLabelThreads) void dweight_label_kernel(
       cur.x += r.x; cur.y += r.y; cur.z += r.z; cur.w += r.w;
       *dst = cur;
     }
+  }
+}
+
+// dweight_label_combine (after dweight_label<LABEL_WINDOW>): block i, if sample i is the first of
+// its class in the whole batch, adds the class's window sums (rows of `part` named by the window
+// heads) in window order; the total goes to row i of `part` (COMPACT, fused step) or is added to
+// dWn[y].  One float4 column per thread.
+template <bool COMPACT>
+__global__ void dweight_label_combine_kernel(int B, int D, const int32_t* __restrict__ yl,
+                                             int64_t k, const int32_t* __restrict__ head,
+                                             int64_t kp, int nwin, float* __restrict__ part,
+                                             float* __restrict__ dW) {
+  const int i = blockIdx.x, col = threadIdx.x;
+  const int32_t y = yl[i];
+  if (y < 0 || (int64_t)y >= k) return;
+  if (head[y] != i || col >= (D >> 2)) return;
+  float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int w = i / kLabelWindow; w < nwin; ++w) {
+    const int32_t h = head[(int64_t)(1 + w) * kp + y];
+    if (h == 0x7fffffff) continue;
+    const float4 o = *reinterpret_cast<const float4*>(part + (int64_t)h * D + col * 4);
+    r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w;
+  }
+  if constexpr (COMPACT) {
+    *reinterpret_cast<float4*>(part + (int64_t)i * D + col * 4) = r;
+  } else {
+    float4* dst = reinterpret_cast<float4*>(dW + (int64_t)y * D + col * 4);
+    float4 cur = *dst;
+    cur.x += r.x; cur.y += r.y; cur.z += r.z; cur.w += r.w;
+    *dst = cur;
   }
 }
 
@@ -1050,6 +1106,8 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   const int Bp = (int)round_up(B, kPadB);
   const int64_t kp = round_up(k, kPadK);
   T* Xn = (T*)c->Xn; T* Xs = (T*)c->Xs; T* Wn = (T*)c->Wn; T* E = (T*)c->E;
+  // windows of the label part (0: the batch fits one window, or the context has no room for them)
+  const int nwin = (B > kLabelWindow && c->label_windows) ? (B + kLabelWindow - 1) / kLabelWindow : 0;
 
   auto norm_kernel = normalize_x_kernel<T, NC>;
   PFC_LAUNCH(c, KID_NORM_X, norm_kernel, dim3((Bp + 3) / 4), dim3(256), 0, X, B, Bp, D,
@@ -1057,7 +1115,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
 
   auto gather_kernel = gather_normalize_w_kernel<T, NC>;
   PFC_LAUNCH(c, KID_GATHER_W, gather_kernel, dim3((unsigned)((kp / 4 + 3) / 4)), dim3(256), 0, W,
-             c->N, idx, k, kp, D, Wn, c->rnormW, c->head, c->err_flag);
+             c->N, idx, k, kp, D, Wn, c->rnormW, c->head, nwin, c->err_flag);
 
   // raise the dynamic LDS limit of this context's kernels once (a context has one precision and
   // one D, hence one instantiation of run)
@@ -1096,8 +1154,29 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     auto combine_kernel = row_combine_kernel<T, NC>;
     PFC_LAUNCH(c, KID_ROW_COMBINE, combine_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowpart,
                tiles_j, B, Bp, D, X, c->rnormX, c->clabel, lp, c->rowmaxpart, c->rowscale,
-               c->dlabel, c->lossrow, c->rowmax, yl, k, c->head, Xs);
+               c->dlabel, c->lossrow, c->rowmax, yl, k, kp, c->head, nwin, Xs);
   }
+  // label part of dWn: added to dW_out, or (compact) left in the side buffer for the fused kernel
+  auto launch_label = [&](bool compact) -> int {
+    if (nwin) {
+      PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel<LABEL_WINDOW>, dim3(B), dim3(kLabelThreads),
+                 0, X, B, D, yl, k, c->head, kp, c->rnormX, c->dlabel, c->dlab);
+      if (compact) {
+        PFC_LAUNCH(c, KID_DW_LABEL_SUM, dweight_label_combine_kernel<true>, dim3(B), dim3(256), 0,
+                   B, D, yl, k, c->head, kp, nwin, c->dlab, dW_out);
+      } else {
+        PFC_LAUNCH(c, KID_DW_LABEL_SUM, dweight_label_combine_kernel<false>, dim3(B), dim3(256), 0,
+                   B, D, yl, k, c->head, kp, nwin, c->dlab, dW_out);
+      }
+    } else if (compact) {
+      PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel<LABEL_COMPACT>, dim3(B), dim3(kLabelThreads),
+                 0, X, B, D, yl, k, c->head, kp, c->rnormX, c->dlabel, c->dlab);
+    } else {
+      PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel<LABEL_ADD>, dim3(B), dim3(kLabelThreads), 0,
+                 X, B, D, yl, k, c->head, kp, c->rnormX, c->dlabel, dW_out);
+    }
+    return PFC_OK;
+  };
   // dweight (+ label part) into dW_out
   auto launch_dweight = [&]() -> int {
     const int tiles_j = (int)(kp / CfgW::BM), tiles_d = Dp / CfgW::BN;
@@ -1119,9 +1198,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                  dim3(xcd_grid(tiles_d, tiles_j)), dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs, D,
                  Dp, k, kp, Bp, dW_out, tiles_j, tiles_d, slabs_total, 1);
     }
-    PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel<false>, dim3(B), dim3(kLabelThreads), 0, X, B,
-               D, yl, k, c->head, c->rnormX, c->dlabel, dW_out);
-    return PFC_OK;
+    return launch_label(false);
   };
   // dfeatures GEMM (split over S) + final reduction, projection, loss
   auto launch_dfeatures = [&]() -> int {
@@ -1159,8 +1236,8 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     if (rc != PFC_OK) return rc;
     return update_impl(c, upd->W, upd->v, idx, k, dW_out, upd->lr, upd->mu);
   }
-  PFC_LAUNCH(c, KID_DW_LABEL, dweight_label_kernel<true>, dim3(B), dim3(kLabelThreads), 0, X, B, D,
-             yl, k, c->head, c->rnormX, c->dlabel, c->dlab);
+  rc = launch_label(true);
+  if (rc != PFC_OK) return rc;
   {
     const int tiles_big = (int)(kp / CfgU::BM);
     const int n_big = tiles_big / c->num_cu * c->num_cu;          // whole rounds

@@ -335,13 +335,23 @@ __device__ __forceinline__ int acc_col(int bn) {
 
 // XCD-aware order of workgroups: consecutive workgroup ids are dealt round-robin to the 8 XCDs
 // (each with its own L2), so the `inner` workgroups that share an operand tile are given ids
-// that land on one XCD.  Returns false for the padding ids of a rounded-up grid.
+// that land on one XCD.  This is done for the outer indices that form whole groups of 8; the
+// remaining outer % 8 (all of them when outer < 8) are laid out plainly, inner index fastest, so
+// that their workgroups spread over all XCDs instead of filling outer % 8 of them.  The grid is
+// exactly inner * outer workgroups; returns false for ids beyond it.
 __device__ __forceinline__ bool xcd_tile(int wg, int inner, int outer, int& o, int& i) {
-  const int xcd = wg & 7, local = wg >> 3;
-  o = (local / inner) * 8 + xcd;
-  i = local % inner;
+  const int full = outer & ~7;
+  if (wg < full * inner) {
+    const int xcd = wg & 7, local = wg >> 3;
+    o = (local / inner) * 8 + xcd;
+    i = local % inner;
+  } else {
+    const int t = wg - full * inner;
+    o = full + t / inner;
+    i = t % inner;
+  }
   return o < outer;
 }
-inline int xcd_grid(int inner, int outer) { return (int)round_up(outer, 8) * inner; }
+inline int xcd_grid(int inner, int outer) { return inner * outer; }
 
 }  // namespace pfc

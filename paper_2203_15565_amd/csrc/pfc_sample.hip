@@ -178,12 +178,20 @@ __global__ void sample_hist_kernel(int64_t N, PhiloxKey key, uint32_t* __restric
   if constexpr (P == 0) {
     if ((int)blockIdx.x >= hist_blocks) {   // marking part of the launch
       const int i = ((int)blockIdx.x - hist_blocks) * kThreads + threadIdx.x;
-      if (i >= B) return;
-      const int64_t y = labels[i];
-      if (y < 0 || y >= N) {
-        atomicOr(err_flag, 1);
-        return;
+      const int64_t y = i < B ? labels[i] : 0;
+      const bool valid = i < B && y >= 0 && y < N;
+      if (i < B && !valid) atomicOr(err_flag, 1);
+      // One lane per distinct label of the wavefront goes on: with long-tailed labels a frequent
+      // class would otherwise bring thousands of atomics onto one word.
+      bool lead = false;
+      unsigned long long todo = __ballot(valid);
+      while (todo) {   // wave-uniform loop over the distinct labels
+        const int src = __ffsll(todo) - 1;
+        const int64_t y0 = __shfl(y, src, 64);
+        lead = lead || (int)(threadIdx.x & 63) == src;
+        todo &= ~__ballot(valid && y == y0);
       }
+      if (!lead) return;
       const uint32_t bit = 1u << (y & 31);
       const uint32_t old = atomicOr(&pos_bits[y >> 5], bit);
       if (!(old & bit)) {   // first to mark class y

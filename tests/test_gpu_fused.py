@@ -39,6 +39,8 @@ CASES = [
     (5_000, 70, 1024, 0.2, binding.PRECISION_BF16, 5_000),      # D = 1024
     (4_000, 33, 768, 0.15, binding.PRECISION_FP32, 40),         # D = 768, duplicates
     (50_000, 4096, 512, 1e-9, binding.PRECISION_BF16, 50_000),  # k = U small, batch sliced
+    (50_000, 3000, 512, 1e-9, binding.PRECISION_FP32, 40),      # three label windows, 40 classes
+    (400_000, 2100, 512, 0.1, binding.PRECISION_BF16, 300),     # one kernel, three label windows
     (6_000, 100, 192, 0.1, binding.PRECISION_BF16, 6_000),      # D a multiple of 64 only
     (50_000, 4096, 128, 1e-9, binding.PRECISION_FP32, 50_000),  # likewise, batch sliced
 ]

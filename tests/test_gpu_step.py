@@ -115,6 +115,15 @@ def test_forward_backward_large_scale(precision):
     _fb_parity(precision, 4000, 96, 512, 0.1, 400.0, 0.5, seed=33, dup=True)
 
 
+@pytest.mark.parametrize("precision", [binding.PRECISION_FP32, binding.PRECISION_BF16])
+def test_forward_backward_batch_of_several_label_windows(precision):
+    """Batches above 1024 samples: the label part of the center gradient is summed per window of
+    1024 samples and the window sums are combined; half of the batch carries one label here, so
+    that class has a sum in every window."""
+    _fb_parity(precision, 20_000, 2500, 512, 0.05, 64.0, 0.5, seed=41, dup=True)
+    _fb_parity(precision, 20_000, 3072, 256, 0.05, 64.0, 0.5, seed=42)
+
+
 def test_forward_backward_minimum_k():
     """k = U (no negatives outside the batch), including k far below one tile."""
     _fb_parity(binding.PRECISION_FP32, 100_000, 24, 512, 1e-5, 64.0, 0.5, seed=14)
