@@ -30,22 +30,22 @@ PEAK_FP32_MFMA_TFLOPS = 157.3  # fp32 MFMA
 # summarised in profiles/headline_step_hbm_traffic.md, keyed by (workload, r, kernel).  None where
 # no counter run has been recorded.
 MEASURED_TRAFFIC_BYTES: dict = {
-    ("headline", 0.1, "gemm_dweight_update"): 2171339070,
-    ("headline", 0.1, "update"): 2115906606,
-    ("headline", 0.1, "gather_normalize_w"): 636323268,
-    ("headline", 0.1, "gemm_logits"): 681939023,
-    ("headline", 0.1, "gemm_dweight"): 902793614,
-    ("headline", 0.1, "gemm_dfeatures"): 700276416,
+    ("headline", 0.1, "gemm_dweight_update"): 2171342916,
+    ("headline", 0.1, "update"): 2115907072,
+    ("headline", 0.1, "gather_normalize_w"): 636338241,
+    ("headline", 0.1, "gemm_logits"): 723901584,
+    ("headline", 0.1, "gemm_dweight"): 905431780,
+    ("headline", 0.1, "gemm_dfeatures"): 700291405,
 }
 
 # Fraction of a GEMM kernel's own cycles in which an MFMA pipe was busy, from the rocprofv3 --pmc
 # run summarised in profiles/headline_step_mfma_lds_counters.md (SQ_VALU_MFMA_BUSY_CYCLES over
 # the kernel's SQ_BUSY_CYCLES: independent of the clock the kernel ran at).
 MEASURED_MFMA_BUSY: dict = {
-    ("headline", 0.1, "gemm_logits"): 0.334,
-    ("headline", 0.1, "gemm_dweight"): 0.379,
-    ("headline", 0.1, "gemm_dfeatures"): 0.589,
-    ("headline", 0.1, "gemm_dweight_update"): 0.194,
+    ("headline", 0.1, "gemm_logits"): 0.352,
+    ("headline", 0.1, "gemm_dweight"): 0.373,
+    ("headline", 0.1, "gemm_dfeatures"): 0.591,
+    ("headline", 0.1, "gemm_dweight_update"): 0.196,
 }
 
 
