@@ -124,6 +124,35 @@ def test_forward_backward_batch_of_several_label_windows(precision):
     _fb_parity(precision, 20_000, 3072, 256, 0.05, 64.0, 0.5, seed=42)
 
 
+@pytest.mark.parametrize("precision", [binding.PRECISION_FP32, binding.PRECISION_BF16])
+def test_forward_backward_smallest_shapes(precision):
+    """One sample; two classes; the shortest rows."""
+    _fb_parity(precision, 5, 1, 64, 1.0, 64.0, 0.5, seed=51)
+    _fb_parity(precision, 2, 1, 512, 1.0, 64.0, 0.5, seed=52)
+    _fb_parity(precision, 2, 3, 128, 1.0, 16.0, 0.2, seed=53)
+
+
+@pytest.mark.parametrize("precision", [binding.PRECISION_FP32, binding.PRECISION_BF16])
+def test_one_class_only(precision):
+    """N = 1: the softmax runs over the label alone, so the loss and every gradient are zero
+    whatever the margin makes of the logit (Eq. 1 with a single term)."""
+    torch = _torch()
+    N, B, D = 1, 3, 256
+    rng = np.random.default_rng(54)
+    X = rng.standard_normal((B, D)).astype(np.float32)
+    W = rng.standard_normal((N, D)).astype(np.float32)
+    labels = np.zeros(B, dtype=np.int64)
+    ctx = binding.Context(N, D, B, 1.0, precision)
+    idx, yl, k = gpu_sample(ctx, labels, 1.0, 0, 0)
+    assert k == 1 and idx[0] == 0 and not yl.any()
+    _say("one class", precision)
+    loss, dX, dWn = gpu_forward_backward(ctx, X, torch.from_numpy(W).cuda(), idx[:k], yl, 64.0, 0.5)
+    o = O.forward_backward(X, W, yl, 64.0, 0.5)
+    assert abs(o["loss"]) < 1e-12 and abs(loss) < 1e-5
+    assert np.abs(dX).max() < 1e-5 and np.abs(dWn[:k]).max() < 1e-5
+    ctx.close()
+
+
 def test_forward_backward_minimum_k():
     """k = U (no negatives outside the batch), including k far below one tile."""
     _fb_parity(binding.PRECISION_FP32, 100_000, 24, 512, 1e-5, 64.0, 0.5, seed=14)
