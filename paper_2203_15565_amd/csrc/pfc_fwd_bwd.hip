@@ -13,9 +13,11 @@
 //   gemm_dfeatures     partial sums of E Wn over slices of S         (MFMA, split over S)
 //   dfeatures_final    reduce slices, scale, label term, project through x -> x/|x|; mean loss
 //
-// Because cosines lie in [-1,1] and s <= 64, exp(s c) lies in [e^-64, e^64] and a row sum over
-// at most 2^31 classes stays below 3.4e38: exp needs no running maximum, and one fixed
-// reference (zero) serves every tile, so p_ij = E_ij / l_i with l_i known only after the GEMM.
+// Cosines lie in [-1,1]: up to s = 64, exp(s c) lies in [e^-64, e^64] and a row sum over at most
+// 2^31 classes stays below 3.4e38, so exp needs no running maximum and one fixed reference (zero)
+// serves every tile, p_ij = E_ij / l_i with l_i known only after the GEMM.  Above s = 64 one more
+// pass of the logit GEMM (gemm_rowmax, row_ref) finds each sample's largest logit first and the
+// softmax runs relative to it.
 // The label column is kept out of E (stored as zero) and handled in fp32 on the side, where
 // (p - 1) and the margin derivative are formed without bf16 rounding.
 #include <limits.h>
@@ -1094,7 +1096,7 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   using CfgF = TileCfg<T, 256, 256, 2, 4, false, false>;   // logits: 256 classes x 256 samples
   using CfgW = TileCfg<T, 256, 256, 2, 4, true, true>;     // dweight: 256 classes x 256 of D
   // fused dweight + update: 128 classes x all 512 columns, half-size slabs so that the wide
-  // operand fits; only used when D == 512
+  // operand fits; this one-kernel form exists for D == 512 only
   using CfgU = TileCfg<T, 128, 512, 2, 4, true, true, 64>;
   using CfgUS = TileCfg<T, 64, 512, 1, 8, true, true, 128>;   // its tiles for the last round
   using CfgX = TileCfg<T, 256, 256, 2, 4, false, true>;    // dfeatures: 256 samples x 256 of D
