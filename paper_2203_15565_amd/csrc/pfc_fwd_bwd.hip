@@ -316,7 +316,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_logits_kernel(
   {
     int ntj, nti;
     const int nb = (int)blockIdx.x + ahead;
-    if (nb < (int)gridDim.x && xcd_tile(nb, tiles_i, tiles_j, ntj, nti)) {
+    if (nb < (int)gridDim.x && (int)(threadIdx.x >> 1) < Cfg::BM &&
+        xcd_tile(nb, tiles_i, tiles_j, ntj, nti)) {
       const int row_bytes = D * (int)sizeof(T);
       const int off = ((nti * 256) % row_bytes) + (threadIdx.x & 1) * 128;
       const char* p = reinterpret_cast<const char*>(Wn + (int64_t)ntj * Cfg::BM * D) +
@@ -1100,6 +1101,10 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
   using CfgU = TileCfg<T, 128, 512, 2, 4, true, true, 64>;
   using CfgUS = TileCfg<T, 64, 512, 1, 8, true, true, 128>;   // its tiles for the last round
   using CfgX = TileCfg<T, 256, 256, 2, 4, false, true>;    // dfeatures: 256 samples x 256 of D
+  // small problems (fewer big tiles than compute units): 128 x 128 tiles, four times
+  // as many workgroups, two of them resident per compute unit (74 KB of LDS each)
+  using CfgFs = TileCfg<T, 128, 128, 2, 4, false, false>;
+  using CfgWs = TileCfg<T, 128, 128, 2, 4, true, true>;
   constexpr int kFusedLds = FusedUpdateLds<CfgU>::LDS > FusedUpdateLds<CfgUS>::LDS
                                 ? FusedUpdateLds<CfgU>::LDS : FusedUpdateLds<CfgUS>::LDS;
   static_assert(kFusedLds <= 160 * 1024, "LDS of one compute unit");
@@ -1132,31 +1137,48 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgW, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgW::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgFs, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgFs::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_logits_kernel<CfgFs, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgFs::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_rowmax_kernel<CfgFs>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgFs::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgWs, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgWs::LDS_BYTES));
+    PFC_HIP(hipFuncSetAttribute((const void*)gemm_dweight_kernel<CfgWs, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgWs::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)gemm_dfeatures_kernel<CfgX>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, CfgX::LDS_BYTES));
     PFC_HIP(hipFuncSetAttribute((const void*)(gemm_dweight_update_kernel<CfgU, CfgUS>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLds));
     c->lds_attr_set = 1;
   }
-  {
-    const int tiles_j = (int)(kp / CfgF::BM), tiles_i = Bp / CfgF::BN;
+  auto launch_logits = [&](auto cfg) -> int {
+    using Cfg = decltype(cfg);
+    const int tiles_j = (int)(kp / Cfg::BM), tiles_i = Bp / Cfg::BN;
     if (lp.rowref) {   // scale above 64: the largest logit of every sample first
-      PFC_LAUNCH(c, KID_GEMM_ROWMAX, gemm_rowmax_kernel<CfgF>, dim3(xcd_grid(tiles_i, tiles_j)),
-                 dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, Dp, k, B, yl, lp, c->rowmaxpart,
+      PFC_LAUNCH(c, KID_GEMM_ROWMAX, gemm_rowmax_kernel<Cfg>, dim3(xcd_grid(tiles_i, tiles_j)),
+                 dim3(Cfg::THREADS), Cfg::LDS_BYTES, Wn, Xn, Dp, k, B, yl, lp, c->rowmaxpart,
                  tiles_j, tiles_i);
       PFC_LAUNCH(c, KID_ROW_REF, row_ref_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowmaxpart,
                  tiles_j, B, Bp, c->rowref);
     }
     // the options (filter, column maxima, reference) have a kernel of their own: the plain one
     // stays lean
-    auto logits_kernel = lp.extras ? gemm_logits_kernel<CfgF, true> : gemm_logits_kernel<CfgF, false>;
+    auto logits_kernel = lp.extras ? gemm_logits_kernel<Cfg, true> : gemm_logits_kernel<Cfg, false>;
     PFC_LAUNCH(c, KID_GEMM_LOGITS, logits_kernel, dim3(xcd_grid(tiles_i, tiles_j)),
-               dim3(CfgF::THREADS), CfgF::LDS_BYTES, Wn, Xn, Dp, k, B, Bp, kp, yl, lp, E, c->rowpart,
+               dim3(Cfg::THREADS), Cfg::LDS_BYTES, Wn, Xn, Dp, k, B, Bp, kp, yl, lp, E, c->rowpart,
                c->rowmaxpart, c->clabel, tiles_j, tiles_i, c->num_cu / 8 * 8);
     auto combine_kernel = row_combine_kernel<T, NC>;
     PFC_LAUNCH(c, KID_ROW_COMBINE, combine_kernel, dim3((Bp + 3) / 4), dim3(256), 0, c->rowpart,
                tiles_j, B, Bp, D, X, c->rnormX, c->clabel, lp, c->rowmaxpart, c->rowscale,
                c->dlabel, c->lossrow, c->rowmax, yl, k, kp, c->head, nwin, Xs);
+    return PFC_OK;
+  };
+  {
+    const bool small = (kp / CfgF::BM) * (Bp / CfgF::BN) < (int64_t)c->num_cu;
+    const int rc = small ? launch_logits(CfgFs{}) : launch_logits(CfgF{});
+    if (rc != PFC_OK) return rc;
   }
   // label part of dWn: added to dW_out, or (compact) left in the side buffer for the fused kernel
   auto launch_label = [&](bool compact) -> int {
@@ -1180,27 +1202,37 @@ int run(pfc_ctx* c, const float* X, const float* W, const int32_t* idx, int64_t 
     return PFC_OK;
   };
   // dweight (+ label part) into dW_out
-  auto launch_dweight = [&]() -> int {
-    const int tiles_j = (int)(kp / CfgW::BM), tiles_d = Dp / CfgW::BN;
-    const int slabs_total = Bp / CfgW::BK;
+  auto launch_dweight_cfg = [&](auto cfg) -> int {
+    using Cfg = decltype(cfg);
+    const int tiles_j = (int)(kp / Cfg::BM), tiles_d = Dp / Cfg::BN;
+    const int slabs_total = Bp / Cfg::BK;
     // slices of the batch when the tiles alone leave most CUs idle; the partial tiles borrow the
     // dfeatures split buffer, which is not in use at that point
-    const int want = dweight_slices<CfgW>(c, tiles_j * tiles_d, Bp, kp);
+    const int want = dweight_slices<Cfg>(c, tiles_j * tiles_d, Bp, kp);
     if (want >= 2) {
       const int slabs_per = (slabs_total + want - 1) / want;
       const int nsp = (slabs_total + slabs_per - 1) / slabs_per;
-      PFC_LAUNCH(c, KID_GEMM_DW, (gemm_dweight_kernel<CfgW, true>),
-                 dim3(xcd_grid(tiles_j * tiles_d, nsp)), dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs,
+      PFC_LAUNCH(c, KID_GEMM_DW, (gemm_dweight_kernel<Cfg, true>),
+                 dim3(xcd_grid(tiles_j * tiles_d, nsp)), dim3(Cfg::THREADS), Cfg::LDS_BYTES, E, Xs,
                  D, Dp, k, kp, Bp, c->dXpart, tiles_j, tiles_d, slabs_per, nsp);
       PFC_LAUNCH(c, KID_DW_REDUCE, dweight_reduce_kernel,
                  dim3((unsigned)((k * D / 4 + 255) / 256)), dim3(256), 0, c->dXpart, nsp, k, kp, D,
                  Dp, dW_out);
     } else {
-      PFC_LAUNCH(c, KID_GEMM_DW, (gemm_dweight_kernel<CfgW, false>),
-                 dim3(xcd_grid(tiles_d, tiles_j)), dim3(CfgW::THREADS), CfgW::LDS_BYTES, E, Xs, D,
+      PFC_LAUNCH(c, KID_GEMM_DW, (gemm_dweight_kernel<Cfg, false>),
+                 dim3(xcd_grid(tiles_d, tiles_j)), dim3(Cfg::THREADS), Cfg::LDS_BYTES, E, Xs, D,
                  Dp, k, kp, Bp, dW_out, tiles_j, tiles_d, slabs_total, 1);
     }
     return launch_label(false);
+  };
+  auto launch_dweight = [&]() -> int {
+    // small tiles only when the big ones, sliced over the batch as far as that goes, still leave
+    // more than half of the compute units idle (a long batch is better cut into slices of big
+    // tiles: half the LDS traffic per flop)
+    const int64_t tiles_big = (kp / CfgW::BM) * (Dp / CfgW::BN);
+    const bool small =
+        tiles_big * dweight_slices<CfgW>(c, (int)tiles_big, Bp, kp) * 2 < (int64_t)c->num_cu;
+    return small ? launch_dweight_cfg(CfgWs{}) : launch_dweight_cfg(CfgW{});
   };
   // dfeatures GEMM (split over S) + final reduction, projection, loss
   auto launch_dfeatures = [&]() -> int {
