@@ -122,6 +122,8 @@ def test_forward_backward_batch_of_several_label_windows(precision):
     that class has a sum in every window."""
     _fb_parity(precision, 20_000, 2500, 512, 0.05, 64.0, 0.5, seed=41, dup=True)
     _fb_parity(precision, 20_000, 3072, 256, 0.05, 64.0, 0.5, seed=42)
+    # 8192 samples, eight windows, most classes in several of them
+    _fb_parity(precision, 3000, 8192, 256, 0.1, 64.0, 0.5, seed=43)
 
 
 @pytest.mark.parametrize("precision", [binding.PRECISION_FP32, binding.PRECISION_BF16])
