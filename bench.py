@@ -263,6 +263,11 @@ def main() -> int:
     sampler = {"ms": round(samp_ms, 5), "launches": sum(1 for n in kern_ms if n.startswith("sample_")),
                "bound": "alu", "achieved": round(samp_ops / (samp_ms * 1e-3) / 1e12, 3), "peak": 39.3,
                "unit": "Tops/s", "frac": round(samp_ops / (samp_ms * 1e-3) / 1e12 / 39.3, 4)}
+    # for comparison, a select that stored one 4-byte score per class and read it once more would
+    # move N*4*2 + N + k*4 bytes: that much time at the HBM peak
+    stored = wl.N * 4 * 2 + wl.N + k * 4
+    sampler["stored_scores_bytes"] = int(stored)
+    sampler["stored_scores_ms_at_hbm_peak"] = round(stored / (PEAK_HBM_GBS * 1e9) * 1e3, 5)
     dominant = max((n for n in kern_ms if n in work), key=lambda n: kern_ms[n])
     roofline = {"kernel": dominant}
     roofline.update({f: kernels[dominant][f] for f in ("bound", "achieved", "peak", "unit", "frac")})
